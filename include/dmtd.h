@@ -1,0 +1,151 @@
+/*
+ * dmtd.h - C ABI of the MI355X (gfx950) decode path for Direct Multi-Token Decoding.
+ *
+ * The library runs cycle-based greedy decoding of a Qwen3-style decoder-only
+ * transformer: each cycle starts with one pass through all layers and continues with
+ * tau-1 passes through only the last n_late ("decoding") layers; the tokens that
+ * skipped the front (encoding + thinking) layers have their front-layer KV entries
+ * refilled by the next cycle's full pass (paper Sec. 2.2, Fig. 3; Eq. 4 for what the
+ * late layers read; Eq. 5 for the LM head; Eq. 7 for the layer count per token).
+ *
+ * Conventions
+ *  - Every pointer is labelled HOST or DEVICE.  The library never allocates or frees
+ *    device memory: the weight blob and the workspace are the caller's, and must stay
+ *    valid and unmodified by others until dmtd_destroy.  Host buffers are borrowed
+ *    only for the duration of a call.
+ *  - All work is enqueued on the one HIP stream given at creation; calls that return
+ *    host data synchronise that stream before returning.  A context is not thread-safe.
+ *  - Every call returns 0 (DMTD_OK) or a negative code; a failed call leaves the
+ *    context's state unchanged.  dmtd_last_error gives a message for the last failure.
+ *  - A batch of sequences shares one prompt length and one cycle phase.
+ *  - Positions are 0-based absolute token positions.
+ *
+ * Weight blob (DEVICE, element type per config.dtype, matrices row-major [out, in],
+ * tensors contiguous in this order): token table [vocab, hidden]; for each layer
+ * attn_norm[hidden], q[n_q_heads*head_dim, hidden], k[n_kv_heads*head_dim, hidden],
+ * v[n_kv_heads*head_dim, hidden], q_norm[head_dim], k_norm[head_dim],
+ * o[hidden, n_q_heads*head_dim], mlp_norm[hidden], gate[intermediate, hidden],
+ * up[intermediate, hidden], down[hidden, intermediate]; final_norm[hidden];
+ * lm_head[vocab, hidden] only when tied_embeddings == 0.
+ */
+#ifndef DMTD_H
+#define DMTD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DMTD_OK          0
+#define DMTD_EINVAL     -1   /* null pointer, bad shape, tau < 1, n_late outside [1, L], token id >= vocab, batch mismatch */
+#define DMTD_ESTATE     -2   /* decode/logits before prefill; prefill twice without reset; n_late changed while tokens await refill */
+#define DMTD_ECAPACITY  -3   /* sequence would exceed max_seq_len; workspace or output buffer too small */
+#define DMTD_EHIP       -4   /* HIP runtime failure (message in dmtd_last_error) */
+
+#define DMTD_DTYPE_F32   0
+#define DMTD_DTYPE_BF16  1
+
+typedef struct dmtd_ctx dmtd_ctx;   /* opaque host object owned by the library */
+
+typedef struct dmtd_config {
+  int32_t n_layers;            /* L */
+  int32_t hidden;              /* d, multiple of 8 */
+  int32_t n_q_heads;           /* multiple of n_kv_heads */
+  int32_t n_kv_heads;
+  int32_t head_dim;            /* 64 or 128 */
+  int32_t intermediate;        /* SwiGLU width, multiple of 8 */
+  int32_t vocab;
+  float   rms_eps;
+  float   rope_theta;
+  int32_t tied_embeddings;     /* 1: the LM head is the token table */
+  int32_t dtype;               /* DMTD_DTYPE_*: storage type of weights and KV cache */
+  int32_t max_batch;
+  int32_t max_seq_len;         /* prompt + generated tokens per sequence */
+  int32_t full_pos_add_embed;  /* 0: late layers read the front output at full positions (tau=1 is ordinary
+                                  decoding); 1: literal Eq. 4, h_emb + h_think at full positions */
+  int32_t use_graphs;          /* 1: each decode step is replayed from a captured hipGraph */
+  int32_t dry_run;             /* 1: no device work at all; only the cycle scheduler runs (host tests) */
+  void*   stream;              /* hipStream_t; NULL = the default stream */
+} dmtd_config;
+
+/* Bytes of DEVICE workspace dmtd_create needs for this configuration (KV caches of all
+ * layers, activations, logits, attention partials, token history, counters).
+ * Returns 0 if the configuration is invalid. */
+size_t dmtd_workspace_bytes(const dmtd_config* cfg);
+
+/* Create a context.  weights_dev: DEVICE weight blob of weights_bytes bytes (layout
+ * above), 16-byte aligned.  workspace_dev: DEVICE, 256-byte aligned, at least
+ * dmtd_workspace_bytes(cfg).  With cfg->dry_run both may be NULL.  On success *out
+ * receives the context.  Errors: DMTD_EINVAL (shape, size or alignment), DMTD_ECAPACITY
+ * (workspace too small), DMTD_EHIP. */
+int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_bytes,
+                void* workspace_dev, size_t workspace_bytes, dmtd_ctx** out);
+
+/* Prefill (Sec. 2.2): all prompt tokens of every sequence pass through all layers,
+ * filling every layer's KV cache for positions 0..prompt_len-1; the last position's
+ * logits give the first generated token, which is the first token of cycle 1.
+ * tokens: HOST int32 [batch, prompt_len] row-major.  first_tokens: HOST int32 [batch],
+ * may be NULL.  n_late is used only under full_pos_add_embed (the embedding is added
+ * again where the late layers start); pass 0 otherwise.
+ * Errors: DMTD_EINVAL, DMTD_ESTATE (already prefilled), DMTD_ECAPACITY. */
+int dmtd_prefill(dmtd_ctx* ctx, const int32_t* tokens, int32_t batch, int32_t prompt_len,
+                 int32_t n_late, int32_t* first_tokens);
+
+/* Run decode steps of cycle length tau with n_late late layers (Sec. 2.2).  If the
+ * current cycle is complete (tau tokens emitted, counting the token prefill emitted
+ * for cycle 1) the call starts a new cycle with a full step: the pending in-cycle
+ * tokens and the newest token pass through the first L - n_late layers together
+ * (refilling those layers' KV), and only the newest continues through the late
+ * layers.  It then runs late-only steps (the newest token's embedding is the late
+ * layers' input, Eq. 4) until the cycle has tau tokens or max_new steps have run in
+ * this call (max_new <= 0: no cap).  So the first call after prefill emits tau-1
+ * tokens and later calls emit tau; tau = 1 is ordinary decoding.
+ * forced_inputs: HOST int32 [batch, n_forced] or NULL.  Step i of this call (i <
+ * n_forced) consumes forced_inputs[b, i] as its input token instead of the previous
+ * step's argmax (teacher forcing); out_tokens still reports every step's argmax.
+ * out_tokens: HOST int32 [batch, out_stride], step i of sequence b at b*out_stride+i;
+ * out_stride must be >= the number of steps the call runs (at most tau).
+ * n_emitted: HOST, receives the number of steps run.
+ * Errors: DMTD_EINVAL, DMTD_ESTATE (no prefill; n_late changed while tokens await
+ * refill), DMTD_ECAPACITY (max_seq_len, out_stride). */
+int dmtd_decode_cycle(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t max_new,
+                      const int32_t* forced_inputs, int32_t n_forced,
+                      int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
+
+/* Copy the logits (Eq. 5) of the most recent step: HOST float32 [batch, vocab],
+ * out_elems >= batch * vocab.  Errors: DMTD_ESTATE before prefill, DMTD_ECAPACITY. */
+int dmtd_logits(dmtd_ctx* ctx, float* out, size_t out_elems);
+
+/* Scheduler state.  n_tok: tokens that have entered the late layers' caches; n_front:
+ * tokens in the front layers' caches (n_tok - n_front await refill); phase: tokens of
+ * the current cycle already emitted; counters[4] (HOST int64): layers traversed by
+ * token-emitting rows, layers traversed by refill rows, tokens emitted by decode
+ * steps, decode steps that were full steps.  Any pointer may be NULL. */
+int dmtd_get_state(const dmtd_ctx* ctx, int32_t* n_tok, int32_t* n_front, int32_t* phase,
+                   int64_t* counters);
+
+/* Schedule trace since the last reset: one record of 4 int32 per (pass, layer group):
+ * pass number (1 = prefill), group (0 = front layers, 1 = late layers), first
+ * position, number of consecutive positions.  buf: HOST, cap_records records.
+ * n_records receives the total number available (which may exceed cap_records). */
+int dmtd_get_trace(const dmtd_ctx* ctx, int32_t* buf, int32_t cap_records, int32_t* n_records);
+
+/* Copy one layer's KV cache rows for positions [0, n_pos) of sequence b to the host as
+ * float32 [2 (K,V), n_kv_heads, n_pos, head_dim] (for cache-indexing tests). */
+int dmtd_read_kv(dmtd_ctx* ctx, int32_t layer, int32_t b, int32_t n_pos, float* out, size_t out_elems);
+
+/* Back to the state right after dmtd_create (caches are treated as empty). */
+int dmtd_reset(dmtd_ctx* ctx);
+
+void dmtd_destroy(dmtd_ctx* ctx);
+
+/* Message for the last failed call on ctx (or, with ctx == NULL, the last failed
+ * dmtd_create on this thread).  Never NULL. */
+const char* dmtd_last_error(const dmtd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMTD_H */

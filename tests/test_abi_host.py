@@ -1,0 +1,159 @@
+"""Host-side checks of the C ABI that need no GPU: exported symbols, argument validation,
+and the cycle scheduler (run in the library's dry-run mode, which launches nothing)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_11958_amd as pkg
+from paper_2510_11958_amd.binding import _Config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def dry(n_layers=4, max_seq_len=64, max_batch=1, **kw):
+    return pkg.Engine(pkg.ModelConfig(n_layers, 64, 4, 2, 64, 96, 50, dtype="fp32", max_seq_len=max_seq_len,
+                                      max_batch=max_batch, dry_run=True, **kw))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "dmtd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(dmtd_[a-z_]+)\s*\(", header))
+    assert {"dmtd_create", "dmtd_prefill", "dmtd_decode_cycle", "dmtd_logits"} <= names
+    lib = pkg.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_config_struct_matches_header_order():
+    header = open(os.path.join(ROOT, "include", "dmtd.h")).read()
+    body = header[header.index("typedef struct dmtd_config {"):header.index("} dmtd_config;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:int32_t|float|void\*)\s+([a-z_]+);", body)
+    assert fields == [f[0] for f in _Config._fields_]
+
+
+def test_invalid_configurations_are_rejected():
+    lib = pkg.load_library()
+    good = pkg.ModelConfig(4, 64, 4, 2, 64, 96, 50, dtype="fp32", dry_run=True)
+    assert lib.dmtd_workspace_bytes(C.byref(good.to_c())) > 0
+    for field, val in [("n_layers", 0), ("hidden", 60), ("head_dim", 48), ("n_q_heads", 3), ("max_seq_len", 1),
+                       ("max_batch", 0), ("intermediate", 100), ("vocab", 1)]:
+        bad = pkg.ModelConfig(**{**good.__dict__, field: val})
+        assert lib.dmtd_workspace_bytes(C.byref(bad.to_c())) == 0, field
+        with pytest.raises(pkg.DmtdError) as e:
+            pkg.Engine(bad)
+        assert e.value.code == pkg.DMTD_EINVAL
+    # without dry_run, null device pointers are an argument error (no HIP call is made)
+    h = C.c_void_p()
+    real = pkg.ModelConfig(**{**good.__dict__, "dry_run": False})
+    assert lib.dmtd_create(C.byref(real.to_c()), None, 0, None, 0, C.byref(h)) == pkg.DMTD_EINVAL
+    assert b"null" in lib.dmtd_last_error(None)
+
+
+def test_fig3_schedule_from_the_library_scheduler():
+    want = []
+    for line in open(os.path.join(GOLDEN, "fig3_schedule.txt")):
+        if line.strip() and not line.startswith("#"):
+            f = line.split()
+            want.append((int(f[0]), f[1], [int(x) for x in f[2:]]))
+    e = dry()
+    e.prefill([[1, 2, 3, 4, 5]])
+    assert e.decode_cycle(3, 1).shape == (1, 2)     # cycle 1: prefill's token + two late-only steps
+    assert e.decode_cycle(3, 1).shape == (1, 3)
+    assert e.decode_cycle(3, 1, max_new=1).shape == (1, 1)
+    assert e.trace() == want
+    s = e.state()
+    assert (s["n_tok"], s["n_front"], s["phase"], s["n_emitted"], s["n_full_steps"]) == (11, 11, 1, 6, 2)
+
+
+@pytest.mark.parametrize("L,n_late,tau", [(36, 8, 3), (36, 8, 4), (28, 4, 2), (4, 1, 2), (36, 12, 4), (36, 8, 1)])
+def test_layer_visit_counters_give_eq7(L, n_late, tau):
+    e = dry(n_layers=L, max_seq_len=256)
+    e.prefill([[1, 2, 3]])
+    e.decode_cycle(tau, n_late)
+    s0 = e.state()
+    for _ in range(7):
+        assert e.decode_cycle(tau, n_late).shape[1] == tau
+    s1 = e.state()
+    toks = s1["n_emitted"] - s0["n_emitted"]
+    plt = (s1["gen_layer_visits"] - s0["gen_layer_visits"]) / (toks * L)
+    assert plt == pytest.approx((L + (tau - 1) * n_late) / (tau * L), abs=1e-15)
+    if (L, n_late, tau) == (36, 8, 3):      # the values the paper prints for MTD3 (Sec. 3.4)
+        assert abs(plt - 0.48) < 0.005 and abs(1 / plt - 2.08) < 0.005
+    # same total load as the vanilla model (Sec. 2.2): each consumed token crosses every layer once
+    consumed = s1["n_tok"] - 3
+    total = s1["gen_layer_visits"] + s1["refill_layer_visits"]
+    assert total == consumed * L - (s1["n_tok"] - s1["n_front"]) * (L - n_late)
+
+
+def test_state_and_argument_errors_leave_state_unchanged():
+    e = dry(max_seq_len=8)
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.decode_cycle(2, 1)
+    assert ex.value.code == pkg.DMTD_ESTATE
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.prefill([[1, 2, 99]])
+    assert ex.value.code == pkg.DMTD_EINVAL and e.state()["n_tok"] == 0
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.prefill([[1] * 8])
+    assert ex.value.code == pkg.DMTD_ECAPACITY
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.prefill([[1, 2], [3, 4]])          # batch above max_batch
+    assert ex.value.code == pkg.DMTD_EINVAL
+    e.prefill([[1, 2, 3, 4, 5, 6]])
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.prefill([[1, 2, 3]])
+    assert ex.value.code == pkg.DMTD_ESTATE
+    before = e.state()
+    for tau, n_late, code in [(0, 1, pkg.DMTD_EINVAL), (2, 0, pkg.DMTD_EINVAL), (2, 5, pkg.DMTD_EINVAL),
+                              (65, 1, pkg.DMTD_EINVAL), (4, 1, pkg.DMTD_ECAPACITY)]:
+        with pytest.raises(pkg.DmtdError) as ex:
+            e.decode_cycle(tau, n_late)
+        assert ex.value.code == code
+        assert e.state() == before
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.decode_cycle(2, 1, forced=[[77]])
+    assert ex.value.code == pkg.DMTD_EINVAL and e.state() == before
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.logits()
+    assert ex.value.code == pkg.DMTD_ESTATE
+    e.decode_cycle(2, 1)                      # one late step: a token now awaits refill
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.decode_cycle(2, 2)                  # n_late may not change now
+    assert ex.value.code == pkg.DMTD_ESTATE
+    e.decode_cycle(1, 1)
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.decode_cycle(1, 1)
+    assert ex.value.code == pkg.DMTD_ECAPACITY
+    e.reset()
+    assert e.state()["n_tok"] == 0 and e.trace() == []
+    e.prefill([[1, 2, 3]])
+    e.decode_cycle(1, 2)                      # after a reset n_late is free again
+
+
+def test_out_stride_and_null_outputs():
+    lib = pkg.load_library()
+    e = dry()
+    e.prefill([[1, 2, 3]])
+    out = np.empty(2, np.int32)
+    n = C.c_int32()
+    p = out.ctypes.data_as(C.POINTER(C.c_int32))
+    assert lib.dmtd_decode_cycle(e._h, 4, 1, 0, None, 0, p, 2, C.byref(n)) == pkg.DMTD_ECAPACITY
+    assert lib.dmtd_decode_cycle(e._h, 4, 1, 0, None, 0, None, 4, C.byref(n)) == pkg.DMTD_EINVAL
+    assert lib.dmtd_decode_cycle(e._h, 4, 1, 2, None, 0, p, 2, C.byref(n)) == pkg.DMTD_OK and n.value == 2
+    assert e.state()["phase"] == 3
+
+
+def test_long_cycles_refill_all_pending_rows():
+    e = dry(max_seq_len=128)
+    e.prefill([[1, 2, 3]])
+    e.decode_cycle(12, 1)          # 11 late steps: 11 tokens await refill
+    assert e.state()["n_tok"] - e.state()["n_front"] == 11
+    e.decode_cycle(12, 1, max_new=1)
+    assert e.trace()[-2:] == [(13, "front", list(range(3, 15))), (13, "late", [14])]
+    assert e.state()["n_tok"] == e.state()["n_front"] == 15
