@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Decode-throughput benchmark of the DMTD hot path on one MI355X.
+
+Workload: the Qwen3-4B-shaped batch-1 configuration (36 layers, 1024-token prompt, 512
+generated tokens, tau=3, n_late=8) with seeded synthetic weights and prompt.  A "step" is
+one decode cycle (one full pass + tau-1 late-only passes = tau tokens).  The same run also
+times tau=1 (ordinary decoding) on the same kernels, the dominant kernel on its own with
+HIP events (roofline), and the CPU oracle on a bounded sample (cpu_baseline).
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(sh, n_late, ctx_full, ctx_late_list, batch):
+    """Bytes one decode cycle must move (each needed weight byte once per step, each live KV byte of a
+    visited layer once per step); returns (cycle bytes, per-layer weight bytes, table bytes)."""
+    e = sh.elem_bytes
+    d, hd = sh.hidden, sh.head_dim
+    per_layer = e * (2 * d + 2 * hd + d * (sh.n_q_heads + 2 * sh.n_kv_heads) * hd + d * sh.n_q_heads * hd
+                     + 3 * d * sh.intermediate)
+    table = e * (sh.vocab * d + d)
+    kv_tok = 2 * sh.n_kv_heads * hd * e * batch      # per layer per cached position
+    total = sh.n_layers * per_layer + table + sh.n_layers * kv_tok * ctx_full
+    for c in ctx_late_list:
+        total += n_late * per_layer + table + n_late * kv_tok * c
+    return total, per_layer, table
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=160, help="timed decode cycles (tau tokens each)")
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graphs", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import dmtd_inputs as di
+    import paper_2510_11958_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the decode path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    wl = di.WORKLOADS[args.workload]
+    sh, B, P, tau, n_late = wl.shape, wl.batch, wl.prompt_len, wl.tau, wl.n_late
+    K, W = args.steps, args.warmup
+    t0 = time.time()
+    blob = di.make_weight_blob(sh, seed=0)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=1)
+    max_seq = P + 1 + (K + W + 2) * max(tau, 1) + 8
+    cfg = pkg.ModelConfig(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.intermediate, sh.vocab,
+                          dtype=sh.dtype, max_batch=B, max_seq_len=max_seq, use_graphs=not args.no_graphs)
+    eng = pkg.Engine(cfg, blob)
+    t_setup = time.time() - t0
+
+    def run(tau_run, cycles, warm):
+        eng.reset()
+        eng.prefill(prompts)
+        eng.decode_cycle(tau_run, n_late)                 # finishes cycle 1 (tau-1 tokens); untimed
+        for _ in range(warm):
+            eng.decode_cycle(tau_run, n_late)
+        torch.cuda.synchronize()
+        ctx0 = eng.state()["n_tok"]
+        t = time.perf_counter()
+        ntok = 0
+        for _ in range(cycles):
+            ntok += eng.decode_cycle(tau_run, n_late).shape[1] * B
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        return ntok, dt, ctx0
+
+    ntok, dt, ctx0 = run(tau, K, W)
+    # tau = 1 on the same kernels, over the same number of tokens
+    ntok1, dt1, _ = run(1, K * tau, W * tau)
+
+    # algorithmic bytes of the timed DMTD cycles (true per-step context)
+    total_bytes = 0
+    for c in range(K):
+        base = ctx0 + c * tau
+        cyc, per_layer, table = algorithmic_bytes(sh, n_late, base + 1, [base + 1 + i for i in range(1, tau)], B)
+        total_bytes += cyc
+    e2e_gbs = total_bytes / dt / 1e9
+
+    # roofline of the dominant kernel: RMSNorm + gate/up + SwiGLU weight stream (49 % of a layer's bytes),
+    # launched once per layer back to back, HIP-event timed on the engine's stream
+    rows = min(tau, 4)
+    reps = 10
+    per = {}
+    for kind, r in (("gateup", rows), ("gateup", 1), ("down", rows), ("qkv", rows), ("oproj", rows), ("lmhead", 1), ("attn", 1)):
+        per[f"{kind}_m{r}"] = eng.time_kernel(kind, r, reps)
+    gu_bytes = 2 * sh.intermediate * sh.hidden * sh.elem_bytes + sh.hidden * sh.elem_bytes
+    achieved = gu_bytes / (per[f"gateup_m{rows}"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": f"gemv_kernel<bf16, M={rows}, SWIGLU, NORM> (RMSNorm + gate/up + SwiGLU)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": gu_bytes, "avg_launch_us": round(per[f"gateup_m{rows}"], 2),
+                "other_kernels_us": {k: round(v, 2) for k, v in per.items()}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(di, blob, sh, tau, n_late)
+
+    out = {
+        "metric": "decode tokens/sec at 1 GPU (DMTD tau vs tau=1) + achieved HBM GB/s fraction",
+        "value": round(ntok / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if sh.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "tau": tau, "n_late": n_late, "batch": B, "prompt_len": P,
+                   "context_at_start": ctx0, "graphs": not args.no_graphs},
+        "tau1_tokens_per_s": round(ntok1 / dt1, 2), "speedup_vs_tau1": round((ntok / dt) / (ntok1 / dt1), 4),
+        "end_to_end": {"algorithmic_GB_per_cycle": round(total_bytes / K / 1e9, 4), "achieved_GBs": round(e2e_gbs, 1),
+                       "frac_of_hbm_peak": round(e2e_gbs / HBM_PEAK_GBS, 4)},
+        "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(t_setup, 1),
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(di, blob, sh, tau, n_late):
+    """The NumPy oracle, as it stands, on this machine's host cores: decode tokens/s on a bounded sample."""
+    import numpy as np
+    from oracle import dmtd_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ocfg = O.OracleConfig(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.intermediate, sh.vocab,
+                          sh.rms_eps, sh.rope_theta, sh.tied_embeddings)
+    big = di.blob_elems(sh) > 1_000_000_000
+    dt = np.float32 if big else np.float64
+    w = O.unpack_weights(blob, ocfg, dt)
+    P = 16
+    orc = O.DmtdOracle(ocfg, w, 64, dt)
+    orc.prefill(di.make_prompts(sh.vocab, 1, P, seed=1)[0])
+    orc.decode_cycle(tau, n_late)
+    t = time.perf_counter()
+    n = 0
+    cycles = 0
+    while time.perf_counter() - t < 12.0 and orc.n_tok + tau < 60:
+        n += len(orc.decode_cycle(tau, n_late))
+        cycles += 1
+    el = time.perf_counter() - t
+    return {"value": round(n / el, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{cycles} cycles of tau={tau}, n_late={n_late} after a {P}-token prompt (not the full prompt), "
+                      f"batch 1, oracle in {'float32' if big else 'float64'}"}
+
+
+if __name__ == "__main__":
+    main()

@@ -136,6 +136,21 @@ int dmtd_get_trace(const dmtd_ctx* ctx, int32_t* buf, int32_t cap_records, int32
  * float32 [2 (K,V), n_kv_heads, n_pos, head_dim] (for cache-indexing tests). */
 int dmtd_read_kv(dmtd_ctx* ctx, int32_t layer, int32_t b, int32_t n_pos, float* out, size_t out_elems);
 
+/* Measurement aid: launch one kernel kind of the decode path back to back, once per layer
+ * (the LM head: once per repetition), reps times over, with `rows` activation rows, on the
+ * context's stream between two HIP events, and return the average duration of one launch
+ * in microseconds.  Activations are whatever the workspace holds; caches, token history and
+ * scheduler state are not modified (the residual stream scratch is).  kind: DMTD_K_*.
+ * Needs a prefilled context (attention reads the current context length).
+ * Errors: DMTD_EINVAL (kind, rows outside [1, 4], reps < 1), DMTD_ESTATE, DMTD_EHIP. */
+#define DMTD_K_QKV     0   /* RMSNorm + fused QKV projection (Sec. 3.1 model; hot-path step a2) */
+#define DMTD_K_OPROJ   1   /* O projection + residual */
+#define DMTD_K_GATEUP  2   /* RMSNorm + gate/up projections + SwiGLU */
+#define DMTD_K_DOWN    3   /* down projection + residual */
+#define DMTD_K_LMHEAD  4   /* final RMSNorm + LM head (Eq. 5) + argmax partials */
+#define DMTD_K_ATTN    5   /* split-K GQA decode attention over the current context */
+int dmtd_time_kernel(dmtd_ctx* ctx, int32_t kind, int32_t rows, int32_t reps, float* avg_us);
+
 /* Back to the state right after dmtd_create (caches are treated as empty). */
 int dmtd_reset(dmtd_ctx* ctx);
 

@@ -62,6 +62,8 @@ def load_library():
     lib.dmtd_get_trace.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, P(C.c_int32)]
     lib.dmtd_read_kv.restype = C.c_int
     lib.dmtd_read_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float), C.c_size_t]
+    lib.dmtd_time_kernel.restype = C.c_int
+    lib.dmtd_time_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
     lib.dmtd_reset.restype = C.c_int
     lib.dmtd_reset.argtypes = [C.c_void_p]
     lib.dmtd_destroy.restype = None
@@ -201,6 +203,14 @@ class Engine:
         out = np.empty((2, self.cfg.n_kv_heads, n_pos, self.cfg.head_dim), np.float32)
         self._check(self.lib.dmtd_read_kv(self._h, layer, b, n_pos, out.ctypes.data_as(C.POINTER(C.c_float)), out.size))
         return out
+
+    KERNEL_KINDS = {"qkv": 0, "oproj": 1, "gateup": 2, "down": 3, "lmhead": 4, "attn": 5}
+
+    def time_kernel(self, kind: str, rows: int = 1, reps: int = 5) -> float:
+        """Average duration (microseconds) of one launch of a kernel kind, HIP-event timed on the engine's stream."""
+        us = C.c_float()
+        self._check(self.lib.dmtd_time_kernel(self._h, self.KERNEL_KINDS[kind], rows, reps, C.byref(us)))
+        return us.value
 
     def reset(self):
         self._check(self.lib.dmtd_reset(self._h))

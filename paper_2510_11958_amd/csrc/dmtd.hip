@@ -363,6 +363,70 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
   return run_head<WT>(c, h_late, 1);   // state goes from P-1 to n_tok = n_front = P
 }
 
+// One launch of one kernel kind on layer l, for dmtd_time_kernel.  Outputs go to scratch
+// buffers only: the QKV/attention/MLP activations, the residual scratch h (never h_late,
+// never the caches, the token history or the scheduler state).
+template <typename WT>
+hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
+  const dmtd_config& cf = c->cfg;
+  const int d = cf.hidden, hd = cf.head_dim;
+  const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * hd, qd = cf.n_q_heads * hd;
+  float* h = (float*)(c->ws + c->o.h);
+  float* qkv = (float*)(c->ws + c->o.qkv);
+  float* attn = (float*)(c->ws + c->o.attn);
+  float* mlp = (float*)(c->ws + c->o.mlp);
+  const LayerW& w = c->layers[l];
+  GemvArgs a{};
+  a.eps = cf.rms_eps;
+  switch (kind) {
+    case DMTD_K_QKV:
+      a.W = w.q; a.gain = w.attn_norm; a.x = h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
+      return gemv_rows<WT, EPI_STORE, true>(c, a, rows);
+    case DMTD_K_OPROJ:
+      a.W = w.o; a.x = attn; a.ldx = qd; a.y = h; a.ldy = d; a.N = d; a.K = qd;
+      return gemv_rows<WT, EPI_RESID, false>(c, a, rows);
+    case DMTD_K_GATEUP:
+      a.W = w.gate; a.W2 = w.up; a.gain = w.mlp_norm; a.x = h; a.ldx = d; a.y = mlp; a.ldy = cf.intermediate;
+      a.N = cf.intermediate; a.K = d;
+      return gemv_rows<WT, EPI_SWIGLU, true>(c, a, rows);
+    case DMTD_K_DOWN:
+      a.W = w.down; a.x = mlp; a.ldx = cf.intermediate; a.y = h; a.ldy = d; a.N = d; a.K = cf.intermediate;
+      return gemv_rows<WT, EPI_RESID, false>(c, a, rows);
+    case DMTD_K_LMHEAD: {
+      // the real LM-head kernel (logits + argmax); a null token history suppresses its token side effects
+      a.W = c->lm_head; a.gain = c->final_norm; a.x = h; a.ldx = d; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
+      a.N = cf.vocab; a.K = d;
+      a.partial = (ArgmaxPartial*)(c->ws + c->o.amax_part);
+      a.counter = (unsigned int*)(c->ws + c->o.amax_ctr);
+      a.tokens = nullptr; a.emitted = nullptr;
+      a.st = (const DevState*)(c->ws + c->o.state);
+      a.s_max = cf.max_seq_len; a.batch = c->batch;
+      return gemv_rows<WT, EPI_LOGITS, true>(c, a, rows);
+    }
+    default: {
+      // attention for `rows` query rows per sequence ending at the newest cached position
+      const int B = c->batch;
+      const int last = c->sched.n_tok - 1;
+      const int r = rows <= last + 1 ? rows : 1;
+      const int n_splits = splits_for(c, last);
+      WT* kc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+      WT* vc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+      dim3 grid(n_splits, cf.n_kv_heads, B);
+      float* po = (float*)(c->ws + c->o.part_o);
+      float* pml = (float*)(c->ws + c->o.part_ml);
+      unsigned int* ctr = (unsigned int*)(c->ws + c->o.att_ctr);
+      const DevState* st = (const DevState*)(c->ws + c->o.state);
+      if (hd == 128)
+        hipLaunchKernelGGL((attn_split_kernel<WT, 128>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr, attn,
+                           qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, (int)POS_EXPLICIT, last - r + 1, r);
+      else
+        hipLaunchKernelGGL((attn_split_kernel<WT, 64>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr, attn,
+                           qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, (int)POS_EXPLICIT, last - r + 1, r);
+      return hipGetLastError();
+    }
+  }
+}
+
 void destroy_graphs(dmtd_ctx* c) {
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
   c->graphs.clear();
@@ -602,6 +666,48 @@ int dmtd_read_kv(dmtd_ctx* c, int32_t layer, int32_t b, int32_t n_pos, float* ou
       std::memcpy(out + i, &u, 4);
     }
   }
+  return DMTD_OK;
+}
+
+int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, float* avg_us) {
+  if (!c) return DMTD_EINVAL;
+  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > kGemvRows || reps < 1) {
+    c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
+  }
+  if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }
+  if (kind == DMTD_K_ATTN && rows > c->max_rows) { c->err = "too many rows for the attention kernel"; return DMTD_EINVAL; }
+  hipEvent_t e0, e1;
+  HIP_TRY(c, hipEventCreate(&e0));
+  HIP_TRY(c, hipEventCreate(&e1));
+  const bool f32 = c->cfg.dtype == DMTD_DTYPE_F32;
+  // rows is per sequence for attention, total activation rows for the projections
+  const int saved_batch = c->batch;
+  long launches = 0;
+  hipError_t e = hipSuccess;
+  for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {   // pass 0 warms up (one repetition)
+    const int n = pass == 0 ? 1 : reps;
+    if (pass == 1) e = hipEventRecord(e0, c->stream);
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+      if (kind == DMTD_K_LMHEAD) {
+        e = f32 ? time_one<float>(c, kind, 0, rows) : time_one<bf16_t>(c, kind, 0, rows);
+        if (pass == 1) launches += 1;
+      } else {
+        for (int l = 0; l < c->cfg.n_layers && e == hipSuccess; ++l) {
+          e = f32 ? time_one<float>(c, kind, l, rows) : time_one<bf16_t>(c, kind, l, rows);
+          if (pass == 1) launches += 1;
+        }
+      }
+    }
+    if (pass == 1 && e == hipSuccess) e = hipEventRecord(e1, c->stream);
+  }
+  c->batch = saved_batch;
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) { c->err = std::string("dmtd_time_kernel: ") + hipGetErrorString(e); return DMTD_EHIP; }
+  *avg_us = ms * 1000.0f / (float)launches;
   return DMTD_OK;
 }
 

@@ -325,7 +325,7 @@ __global__ void __launch_bounds__(1024) gemv_kernel(GemvArgs a) {
             const int oi = __shfl_xor(i, o, 64);
             if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
           }
-          if (lane == 0) {
+          if (lane == 0 && a.tokens) {      // a null history = measurement launch: no token side effects
             const int b = a.m0 + m;
             a.emitted[step * a.batch + b] = i;
             if (pos + 1 < a.s_max && pos + 1 >= forced_until) a.tokens[(size_t)b * a.s_max + pos + 1] = i;
