@@ -31,7 +31,7 @@ struct LayerW {
 
 struct Ws {   // device workspace carve-up (byte offsets)
   size_t kv, kv_layer_stride, kv_v_off;
-  size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, att_ctr, amax_part, amax_ctr;
+  size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, att_ctr, amax;
   size_t tokens, emitted, forced, state, inv_freq, scratch_f32;
   size_t total;
 };
@@ -47,7 +47,6 @@ struct dmtd_ctx {
   int num_cus = 256;
   int batch = 0;              // batch of the current sequence set (after prefill)
   int max_rows = 0;           // rows per sequence a pass may carry
-  int n_splits_cap = 0;
   const char* wbase = nullptr;
   char* ws = nullptr;
   Ws o{};
@@ -55,7 +54,7 @@ struct dmtd_ctx {
   const void* final_norm = nullptr;
   const void* lm_head = nullptr;
   std::vector<LayerW> layers;
-  std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, split bucket)
+  std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late)
   bool have_logits = false;
 };
 
@@ -97,7 +96,7 @@ Ws layout(const dmtd_config& c) {
   const size_t B = c.max_batch, S = c.max_seq_len, d = c.hidden, hd = c.head_dim;
   const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * hd, qd = (size_t)c.n_q_heads * hd;
   const size_t rows = B * rows_cap(c);
-  const size_t splits = (S + ATT_KEYS - 1) / ATT_KEYS;
+  const size_t splits = ATT_MAX_SPLITS;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t kv_one = B * c.n_kv_heads * S * hd * e;       // K (or V) of one layer
@@ -113,8 +112,7 @@ Ws layout(const dmtd_config& c) {
   w.part_o = take(B * c.n_kv_heads * splits * QV_MAX * hd * 4);
   w.part_ml = take(B * c.n_kv_heads * splits * QV_MAX * 2 * 4);
   w.att_ctr = take(B * c.n_kv_heads * 4);
-  w.amax_part = take((size_t)4096 * kGemvRows * sizeof(ArgmaxPartial));
-  w.amax_ctr = take(256);
+  w.amax = take(B * 8);
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
   w.forced = take((size_t)kMaxTau * B * 4);
@@ -138,28 +136,34 @@ Ws layout(const dmtd_config& c) {
 
 template <typename WT, int M, int EPI, bool NORM>
 hipError_t launch_gemv(dmtd_ctx* c, GemvArgs a) {
-  const size_t lds = (size_t)M * a.K * 4;
-  auto kern = gemv_kernel<WT, M, EPI, NORM>;
-  static size_t configured = 0;
-  if (lds > 48 * 1024 && lds > configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
-    if (e != hipSuccess) return e;
-    configured = 160 * 1024;
+  // narrow outputs with long rows: the waves of a block split K
+  if constexpr ((EPI == EPI_RESID || EPI == EPI_STORE) && !NORM) {
+    if (a.K >= 1024 && a.K <= 4 * GEMV_ITS * 512 && a.N <= 8192) {
+      hipLaunchKernelGGL((gemv_ksplit_kernel<WT, M, EPI>), dim3((a.N + 7) / 8), dim3(256), 0, c->stream, a);
+      return hipGetLastError();
+    }
   }
+  const size_t lds = (size_t)M * a.K * 4;
+  auto kern = gemv_rows_kernel<WT, M, EPI, NORM>;
+  static bool configured = false;
+  if (lds > 48 * 1024 && !configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  if (lds > 160 * 1024 - 4096) return hipErrorInvalidValue;
   constexpr int RPW = (EPI == EPI_SWIGLU) ? 2 : 4;
   const int tasks = (a.N + RPW - 1) / RPW;
-  // one resident block per CU when the activation rows fill most of the LDS, else several
-  int nt = 256, per_cu = 4;
-  if (lds > 72 * 1024) { nt = 1024; per_cu = 1; }
-  else if (lds > 36 * 1024) { nt = 512; per_cu = 2; }
-  else if (lds > 24 * 1024) { nt = 256; per_cu = 4; }
-  const int nw = nt / 64;
-  int blocks = (tasks + nw - 1) / nw;
-  const int cap = c->num_cus * per_cu;
-  if (blocks > cap) blocks = cap;
-  if (blocks > 4096) blocks = 4096;
+  // resident blocks per CU: bounded by registers (3 blocks of 4 waves) and by the LDS the rows take
+  int per_cu = (int)((160 * 1024 - 4096) / (lds + 1024));
+  if (per_cu > 3) per_cu = 3;
+  if (per_cu < 1) per_cu = 1;
+  // every wave gets the same number of tasks (k), as far as the row count allows
+  const int waves_cap = c->num_cus * per_cu * 4;
+  const int k = (tasks + waves_cap - 1) / waves_cap;
+  int blocks = (tasks + 4 * k - 1) / (4 * k);
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(nt), lds, c->stream, a);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, c->stream, a);
   return hipGetLastError();
 }
 
@@ -171,7 +175,7 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
     GemvArgs g = a;
     g.x = a.x + (size_t)m0 * a.ldx;
     g.y = a.y + (size_t)m0 * a.ldy;
-    g.m0 = m0;
+    if (a.amax) g.amax = a.amax + m0;
     hipError_t e;
     switch (m) {
       case 1: e = launch_gemv<WT, 1, EPI, NORM>(c, g); break;
@@ -184,8 +188,40 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
   return hipSuccess;
 }
 
+template <typename WT, int HD, int QVT>
+void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r) {
+  const dmtd_config& cf = c->cfg;
+  const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
+  const WT* kc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  const WT* vc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  // enough splits to put about two blocks on every CU, whatever the batch
+  int ns = 2 * c->num_cus / (cf.n_kv_heads * B);
+  if (ns > ATT_MAX_SPLITS) ns = ATT_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  hipLaunchKernelGGL((attn_decode_kernel<WT, HD, QVT>), dim3(ns, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv, kc, vc,
+                     (float*)(c->ws + c->o.part_o), (float*)(c->ws + c->o.part_ml), (unsigned int*)(c->ws + c->o.att_ctr),
+                     attn, qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, (const DevState*)(c->ws + c->o.state), sel, offset, r);
+}
+
 template <typename WT>
-hipError_t run_layers(dmtd_ctx* c, int l0, int l1, float* h, int r, int sel, int explicit_pos, int n_splits,
+hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r) {
+  const dmtd_config& cf = c->cfg;
+  const int qv = r * (cf.n_q_heads / cf.n_kv_heads);
+  if (qv > QV_MAX) return hipErrorInvalidValue;
+  if (cf.head_dim == 128) {
+    if (qv <= 4) launch_attention_t<WT, 128, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qv <= 8) launch_attention_t<WT, 128, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_t<WT, 128, 16>(c, l, qkv, attn, sel, offset, r);
+  } else {
+    if (qv <= 4) launch_attention_t<WT, 64, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qv <= 8) launch_attention_t<WT, 64, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_t<WT, 64, 16>(c, l, qkv, attn, sel, offset, r);
+  }
+  return hipGetLastError();
+}
+
+template <typename WT>
+hipError_t run_layers(dmtd_ctx* c, int l0, int l1, float* h, int r, int sel, int explicit_pos,
                       int add_embed_at /* layer before which the embedding is re-added, or -1 */) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, rows = B * r, d = cf.hidden, hd = cf.head_dim;
@@ -213,18 +249,7 @@ hipError_t run_layers(dmtd_ctx* c, int l0, int l1, float* h, int r, int sel, int
                        qkv, nqkv, w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, cf.n_q_heads,
                        cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps, st, sel, explicit_pos, r);
     // a4: split-K GQA attention + merge
-    {
-      dim3 grid(n_splits, cf.n_kv_heads, B);
-      float* po = (float*)(c->ws + c->o.part_o);
-      float* pml = (float*)(c->ws + c->o.part_ml);
-      unsigned int* ctr = (unsigned int*)(c->ws + c->o.att_ctr);
-      if (hd == 128)
-        hipLaunchKernelGGL((attn_split_kernel<WT, 128>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr,
-                           attn, qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, sel, explicit_pos, r);
-      else
-        hipLaunchKernelGGL((attn_split_kernel<WT, 64>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr,
-                           attn, qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, sel, explicit_pos, r);
-    }
+    if ((e = launch_attention<WT>(c, l, qkv, attn, sel, explicit_pos, r)) != hipSuccess) return e;
     // a5: O projection + residual
     a = GemvArgs{};
     a.W = w.o; a.x = attn; a.ldx = qd; a.y = h; a.ldy = d; a.N = d; a.K = qd;
@@ -251,31 +276,20 @@ hipError_t run_head(dmtd_ctx* c, const float* h_rows, int full) {
   a.eps = cf.rms_eps;
   a.W = c->lm_head; a.gain = c->final_norm; a.x = h_rows; a.ldx = cf.hidden;
   a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab; a.N = cf.vocab; a.K = cf.hidden;
-  a.partial = (ArgmaxPartial*)(c->ws + c->o.amax_part);
-  a.counter = (unsigned int*)(c->ws + c->o.amax_ctr);
-  a.tokens = (int*)(c->ws + c->o.tokens);
-  a.emitted = (int*)(c->ws + c->o.emitted);
-  a.st = (const DevState*)(c->ws + c->o.state);
-  a.s_max = cf.max_seq_len; a.batch = c->batch;
+  a.amax = (unsigned long long*)(c->ws + c->o.amax);
   hipError_t e = gemv_rows<WT, EPI_LOGITS, true>(c, a, c->batch);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, c->stream, (DevState*)(c->ws + c->o.state), full);
+  hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state),
+                     (unsigned long long*)(c->ws + c->o.amax), (int*)(c->ws + c->o.tokens), (int*)(c->ws + c->o.emitted),
+                     cf.max_seq_len, c->batch, full, 1);
   return hipGetLastError();
-}
-
-int splits_for(const dmtd_ctx* c, int last_pos) {
-  // blocks launched along the key axis; rounded up to a bucket so one captured graph serves many steps
-  int need = last_pos / ATT_KEYS + 1;
-  int bucket = (need + 3) / 4 * 4;
-  if (bucket > c->n_splits_cap) bucket = c->n_splits_cap;
-  return bucket;
 }
 
 // One decode step (Sec. 2.2).  Full: embed the pending rows and the newest row, run the front
 // layers on all of them, keep the newest row, run the late layers on it.  Late: embed the
 // newest token and run the late layers only (Eq. 4, m = 0).
 template <typename WT>
-hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late, int n_splits) {
+hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, d = cf.hidden, F = cf.n_layers - n_late;
   float* h = (float*)(c->ws + c->o.h);
@@ -291,7 +305,7 @@ hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late, int n_splits)
       rc = r - c0 < c->max_rows ? r - c0 : c->max_rows;
       hipLaunchKernelGGL(embed_kernel<WT>, dim3(B * rc), dim3(256), 0, c->stream, (const WT*)c->embed, tokens,
                          cf.max_seq_len, st, (int)POS_NFRONT, c0, rc, d, h);
-      if ((e = run_layers<WT>(c, 0, F, h, rc, POS_NFRONT, c0, n_splits, -1)) != hipSuccess) return e;
+      if ((e = run_layers<WT>(c, 0, F, h, rc, POS_NFRONT, c0, -1)) != hipSuccess) return e;
     }
     hipLaunchKernelGGL(take_last_rows_kernel<WT>, dim3(B), dim3(256), 0, c->stream, h, h_late, rc, d,
                        cf.full_pos_add_embed ? 1 : 0, (const WT*)c->embed, tokens, cf.max_seq_len, st, (int)POS_NFRONT,
@@ -300,27 +314,26 @@ hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late, int n_splits)
     hipLaunchKernelGGL(embed_kernel<WT>, dim3(B), dim3(256), 0, c->stream, (const WT*)c->embed, tokens, cf.max_seq_len, st,
                        (int)POS_NTOK, 0, 1, d, h_late);
   }
-  if ((e = run_layers<WT>(c, F, cf.n_layers, h_late, 1, POS_NTOK, 0, n_splits, -1)) != hipSuccess) return e;
+  if ((e = run_layers<WT>(c, F, cf.n_layers, h_late, 1, POS_NTOK, 0, -1)) != hipSuccess) return e;
   return run_head<WT>(c, h_late, full ? 1 : 0);
 }
 
-hipError_t enqueue_step_any(dmtd_ctx* c, bool full, int r, int n_late, int n_splits) {
-  return c->cfg.dtype == DMTD_DTYPE_F32 ? enqueue_step<float>(c, full, r, n_late, n_splits)
-                                        : enqueue_step<bf16_t>(c, full, r, n_late, n_splits);
+hipError_t enqueue_step_any(dmtd_ctx* c, bool full, int r, int n_late) {
+  return c->cfg.dtype == DMTD_DTYPE_F32 ? enqueue_step<float>(c, full, r, n_late)
+                                        : enqueue_step<bf16_t>(c, full, r, n_late);
 }
 
 int run_step(dmtd_ctx* c, const Step& s, int n_late) {
-  const int n_splits = splits_for(c, s.pos);
   if (!c->cfg.use_graphs) {
-    HIP_TRY(c, enqueue_step_any(c, s.full, s.rows, n_late, n_splits));
+    HIP_TRY(c, enqueue_step_any(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, n_splits);
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
     HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-    hipError_t e = enqueue_step_any(c, s.full, s.rows, n_late, n_splits);
+    hipError_t e = enqueue_step_any(c, s.full, s.rows, n_late);
     hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
     if (e != hipSuccess || e2 != hipSuccess) {
       if (graph) (void)hipGraphDestroy(graph);
@@ -354,8 +367,7 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
     const int r = P - p0 < chunk ? P - p0 : chunk;
     hipLaunchKernelGGL(embed_kernel<WT>, dim3(B * r), dim3(256), 0, c->stream, (const WT*)c->embed, tokens, cf.max_seq_len,
                        st, (int)POS_EXPLICIT, p0, r, d, h);
-    const int n_splits = (p0 + r - 1) / ATT_KEYS + 1;
-    if ((e = run_layers<WT>(c, 0, cf.n_layers, h, r, POS_EXPLICIT, p0, n_splits, add_at)) != hipSuccess) return e;
+    if ((e = run_layers<WT>(c, 0, cf.n_layers, h, r, POS_EXPLICIT, p0, add_at)) != hipSuccess) return e;
     r_last = r;
   }
   hipLaunchKernelGGL(take_last_rows_kernel<WT>, dim3(B), dim3(256), 0, c->stream, h, h_late, r_last, d, 0,
@@ -396,33 +408,22 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
       // the real LM-head kernel (logits + argmax); a null token history suppresses its token side effects
       a.W = c->lm_head; a.gain = c->final_norm; a.x = h; a.ldx = d; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
       a.N = cf.vocab; a.K = d;
-      a.partial = (ArgmaxPartial*)(c->ws + c->o.amax_part);
-      a.counter = (unsigned int*)(c->ws + c->o.amax_ctr);
-      a.tokens = nullptr; a.emitted = nullptr;
-      a.st = (const DevState*)(c->ws + c->o.state);
-      a.s_max = cf.max_seq_len; a.batch = c->batch;
-      return gemv_rows<WT, EPI_LOGITS, true>(c, a, rows);
+      a.amax = (unsigned long long*)(c->ws + c->o.amax);
+      {
+        hipError_t e = gemv_rows<WT, EPI_LOGITS, true>(c, a, rows);
+        if (e != hipSuccess) return e;
+        // clear the selection keys again without touching tokens or state
+        hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state),
+                           (unsigned long long*)(c->ws + c->o.amax), (int*)nullptr, (int*)nullptr, cf.max_seq_len, rows, 0, 0);
+        return hipGetLastError();
+      }
+
     }
     default: {
       // attention for `rows` query rows per sequence ending at the newest cached position
-      const int B = c->batch;
       const int last = c->sched.n_tok - 1;
       const int r = rows <= last + 1 ? rows : 1;
-      const int n_splits = splits_for(c, last);
-      WT* kc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
-      WT* vc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
-      dim3 grid(n_splits, cf.n_kv_heads, B);
-      float* po = (float*)(c->ws + c->o.part_o);
-      float* pml = (float*)(c->ws + c->o.part_ml);
-      unsigned int* ctr = (unsigned int*)(c->ws + c->o.att_ctr);
-      const DevState* st = (const DevState*)(c->ws + c->o.state);
-      if (hd == 128)
-        hipLaunchKernelGGL((attn_split_kernel<WT, 128>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr, attn,
-                           qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, (int)POS_EXPLICIT, last - r + 1, r);
-      else
-        hipLaunchKernelGGL((attn_split_kernel<WT, 64>), grid, dim3(256), 0, c->stream, qkv, nqkv, kc, vc, po, pml, ctr, attn,
-                           qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, c->n_splits_cap, st, (int)POS_EXPLICIT, last - r + 1, r);
-      return hipGetLastError();
+      return launch_attention<WT>(c, l, qkv, attn, (int)POS_EXPLICIT, last - r + 1, r);
     }
   }
 }
@@ -470,7 +471,6 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   c->sched.n_layers = cfg->n_layers;
   c->sched.max_seq_len = cfg->max_seq_len;
   c->max_rows = rows_cap(*cfg);
-  c->n_splits_cap = (cfg->max_seq_len + ATT_KEYS - 1) / ATT_KEYS;
   if (!cfg->dry_run) {
     c->wbase = (const char*)weights_dev;
     c->ws = (char*)workspace_dev;
@@ -500,7 +500,7 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
     for (size_t i = 0; i < hd / 2; ++i) inv[i] = std::pow((double)cfg->rope_theta, -2.0 * (double)i / (double)hd);
     hipError_t e = hipMemcpyAsync(c->ws + lay.inv_freq, inv.data(), inv.size() * 8, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.att_ctr, 0, (size_t)cfg->max_batch * cfg->n_kv_heads * 4, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax_ctr, 0, 256, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)cfg->max_batch * 8, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, 256, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
@@ -676,6 +676,7 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
   }
   if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }
   if (kind == DMTD_K_ATTN && rows > c->max_rows) { c->err = "too many rows for the attention kernel"; return DMTD_EINVAL; }
+  if (kind == DMTD_K_LMHEAD && rows > c->batch) { c->err = "the LM head carries one row per sequence"; return DMTD_EINVAL; }
   hipEvent_t e0, e1;
   HIP_TRY(c, hipEventCreate(&e0));
   HIP_TRY(c, hipEventCreate(&e1));
