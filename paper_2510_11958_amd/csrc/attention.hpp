@@ -10,10 +10,16 @@
 // softmax (max shared across the wave by shuffles, sum and output per lane group) and
 // accumulates p*V for the 8 output dims its lanes own.  At the end the lane groups of a
 // wave are summed by shuffles, the 4 waves merge through LDS, and the split's
-// (max, sum, unnormalised output) go to a partials buffer; the last block to finish for a
-// (b, g) merges the splits in split order and writes the normalised output.
+// (max, sum, unnormalised output) go to a partials buffer.  A second, small kernel merges
+// the splits in split order (deterministic) and writes the normalised output; the kernel
+// boundary makes the partials visible across the chip without fences or atomics.
 //
-// The number of splits is the launch's grid.x; the keys per split follow from the current
+// Rows can be spread over blocks: a block carries QVT/GQ rows, and grid.x enumerates
+// (split, row group).  With a short context the K/V re-reads this causes are cheap (they
+// hit in L2) and the smaller per-block register footprint wins; with a long context the
+// caller picks a larger QVT so that all rows share one pass over K and V.
+//
+// The number of splits is fixed at launch; the keys per split follow from the current
 // context length, which is read from the device state, so a captured launch stays valid
 // as the sequence grows.
 #pragma once
@@ -21,40 +27,53 @@
 
 namespace dmtd {
 
-constexpr int QV_MAX = 16;         // query vectors per KV head a launch can carry
+constexpr int QV_MAX = 16;         // query vectors per KV head one block can carry (and query heads per KV head)
 constexpr int ATT_MAX_SPLITS = 64;
+
+// Keys a block covers per iteration: 16 lane groups x 4 keys (head_dim 128) or 32 x 4 (head_dim 64).
+template <int HD> struct AttKeysPerIter { static constexpr int value = 4 * (64 / (HD / 8)) * 4; };
+
+// Keys per split for a launch whose last row sees ctx keys (a multiple of the block
+// iteration); the split kernel and the merge kernel must agree on it.
+__device__ __forceinline__ int att_keys_per_split(int ctx, int n_splits, int kpi) {
+  return ((ctx + n_splits - 1) / n_splits + kpi - 1) / kpi * kpi;
+}
 
 template <typename CT, int HD, int QVT>
 __global__ void __launch_bounds__(256) attn_decode_kernel(
     const float* __restrict__ qkv, int ldq, const CT* __restrict__ kc, const CT* __restrict__ vc,
-    float* __restrict__ part_o, float* __restrict__ part_ml, unsigned int* __restrict__ counters,
-    float* __restrict__ out, int ldo, int nh, int nkv, int s_max,
-    const DevState* st, int sel, int offset, int r) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, int n_splits, int qv_stride,
+    const DevState* st, int sel, int offset, int r_total) {
   typedef typename Elem<CT>::Raw Raw;
   constexpr int LPK = HD / 8;          // lanes per key (16 or 8)
   constexpr int GPW = 64 / LPK;        // lane groups per wave (4 or 8)
   constexpr int NG = 4 * GPW;          // lane groups per block
   constexpr int U = 4;                 // keys per lane group per iteration
   constexpr int KPI = NG * U;          // keys per block iteration
+  static_assert(KPI == AttKeysPerIter<HD>::value, "block iteration size");
   constexpr int USH = LPK == 16 ? 2 : 1;   // after the score reduction, lane slice sl holds key u = sl >> USH
 
-  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int g = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int GQ = nh / nkv, QV = r * GQ;
-  const int pos0 = row_base(st, sel, offset);
-  const int ctx = pos0 + r;                                    // keys 0 .. ctx-1 are visible to the last row
-  const int kps = ((ctx + (int)gridDim.x - 1) / (int)gridDim.x + KPI - 1) / KPI * KPI;   // keys per split
-  const int n_act = (ctx + kps - 1) / kps;
+  const int GQ = nh / nkv;
+  const int rpb = QVT / GQ;                                    // rows per block
+  const int n_rg = (r_total + rpb - 1) / rpb;
+  const int split = blockIdx.x / n_rg, rg = blockIdx.x % n_rg;
+  const int r = min(rpb, r_total - rg * rpb), QV = r * GQ;
+  const int pos_first = row_base(st, sel, offset);
+  const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
+  const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
+  const int kps = att_keys_per_split(pos_first + r_total, n_splits, KPI);
   const int key_begin = split * kps, key_end = min(ctx, key_begin + kps);
   const float scale = rsqrtf((float)HD);
 
   __shared__ float wacc[4][QVT][HD];
   __shared__ float wm[4][QVT], wl[4][QVT];
-  __shared__ bool is_last;
 
-  const size_t slot = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
-  float* my_o = part_o + (slot + split) * QVT * HD;
-  float* my_ml = part_ml + (slot + split) * QVT * 2;
+  // partials are indexed by the launch-wide query-vector number row * GQ + head
+  const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
+  float* my_o = part_o + slot * HD;
+  float* my_ml = part_ml + slot * 2;
 
   if (key_begin < ctx) {
     const int sl = lane % LPK, grp = wave * GPW + lane / LPK;
@@ -63,7 +82,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
 #pragma unroll
     for (int qv = 0; qv < QVT; ++qv) {
       if (qv < QV) {
-        const float* qp = qkv + (size_t)(b * r + qv / GQ) * ldq + (size_t)(g * GQ + qv % GQ) * HD + sl * 8;
+        const float* qp = qkv + (size_t)(b * r_total + rg * rpb + qv / GQ) * ldq + (size_t)(g * GQ + qv % GQ) * HD + sl * 8;
         const float4 qa = *(const float4*)qp, qb = *(const float4*)(qp + 4);
         q[qv][0] = qa.x * scale; q[qv][1] = qa.y * scale; q[qv][2] = qa.z * scale; q[qv][3] = qa.w * scale;
         q[qv][4] = qb.x * scale; q[qv][5] = qb.y * scale; q[qv][6] = qb.z * scale; q[qv][7] = qb.w * scale;
@@ -184,31 +203,52 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
     }
   }
 
-  // the last block of this (b, g) to arrive merges the splits, in split order
-  __threadfence();
-  __syncthreads();
-  unsigned int* ctr = counters + (size_t)b * nkv + g;
-  if (tid == 0) is_last = (atomicAdd(ctr, 1u) == gridDim.x - 1);
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  const float* po = part_o + slot * QVT * HD;
-  const float* pml = part_ml + slot * QVT * 2;
-  for (int e = tid; e < QV * HD; e += 256) {
-    const int qv = e / HD, d = e % HD, i = qv / GQ, j = qv % GQ;
-    float mm = -INFINITY;
-    for (int s2 = 0; s2 < n_act; ++s2) mm = fmaxf(mm, pml[((size_t)s2 * QVT + qv) * 2]);
-    float ll = 0.f, o = 0.f;
-    for (int s2 = 0; s2 < n_act; ++s2) {
-      const float ms = pml[((size_t)s2 * QVT + qv) * 2];
-      if (ms == -INFINITY) continue;
-      const float f = __expf(ms - mm);
-      ll += f * pml[((size_t)s2 * QVT + qv) * 2 + 1];
-      o += f * po[((size_t)s2 * QVT + qv) * HD + d];
-    }
-    out[(size_t)(b * r + i) * ldo + (size_t)(g * GQ + j) * HD + d] = o / ll;
+}
+
+// Merge the splits' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
+// f_s = exp(m_s - max_s m_s), splits taken in order.  One block per (row, KV head, sequence).
+template <int HD>
+__global__ void __launch_bounds__(256) attn_merge_kernel(
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, float* __restrict__ out, int ldo,
+    int nh, int nkv, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
+  const int i = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int GQ = nh / nkv;
+  const int pos_first = row_base(st, sel, offset);
+  const int kps = att_keys_per_split(pos_first + r_total, n_splits, AttKeysPerIter<HD>::value);
+  const int n_act = (pos_first + i + 1 + kps - 1) / kps;          // splits that hold keys visible to row i
+  __shared__ float f_s[ATT_MAX_SPLITS][QV_MAX];
+  __shared__ float inv_l[QV_MAX];
+  const size_t slot0 = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
+  for (int e = tid; e < n_act * GQ; e += 256) {
+    const int s2 = e / GQ, j = e % GQ;
+    f_s[s2][j] = part_ml[((slot0 + s2) * qv_stride + i * GQ + j) * 2];
   }
-  if (tid == 0) *ctr = 0u;
+  __syncthreads();
+  if (tid < GQ) {
+    float mm = -INFINITY;
+    for (int s2 = 0; s2 < n_act; ++s2) mm = fmaxf(mm, f_s[s2][tid]);
+    float ll = 0.f;
+    for (int s2 = 0; s2 < n_act; ++s2) {
+      const float f = (f_s[s2][tid] == -INFINITY) ? 0.f : __expf(f_s[s2][tid] - mm);
+      ll += f * part_ml[((slot0 + s2) * qv_stride + i * GQ + tid) * 2 + 1];
+      f_s[s2][tid] = f;
+    }
+    inv_l[tid] = 1.0f / ll;
+  }
+  __syncthreads();
+  for (int e = tid; e < GQ * HD; e += 256) {
+    const int j = e / HD, d = e % HD;
+    const float* po = part_o + ((slot0 * qv_stride) + i * GQ + j) * HD + d;
+    float o = 0.f;
+#pragma unroll 8
+    for (int s2 = 0; s2 < n_act; ++s2) {
+      const float f = f_s[s2][j];
+      const float v = po[(size_t)s2 * qv_stride * HD];
+      o += (f == 0.f) ? 0.f : f * v;      // splits without visible keys hold stale partials: weight 0, value ignored
+    }
+    out[(size_t)(b * r_total + i) * ldo + (size_t)(g * GQ + j) * HD + d] = o * inv_l[j];
+  }
 }
 
 }  // namespace dmtd

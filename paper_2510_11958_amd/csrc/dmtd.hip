@@ -10,6 +10,7 @@
 #include <map>
 #include <string>
 #include <tuple>
+#include <type_traits>
 #include <vector>
 
 #include "kernels.hpp"
@@ -21,7 +22,10 @@ namespace {
 
 constexpr int kMaxTau = 64;          // steps per decode call (size of the emitted-token buffer)
 constexpr int kGemvRows = 4;         // activation rows per weight-streaming pass
-constexpr int kPrefillChunk = 4;     // prompt positions per prefill pass (per sequence)
+constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
+constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
+constexpr int kMfmaRows = 16;        // activation rows per MFMA weight-streaming pass
+constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 
 thread_local std::string g_create_error;
 
@@ -31,7 +35,7 @@ struct LayerW {
 
 struct Ws {   // device workspace carve-up (byte offsets)
   size_t kv, kv_layer_stride, kv_v_off;
-  size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, att_ctr, amax;
+  size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, amax;
   size_t tokens, emitted, forced, state, inv_freq, scratch_f32;
   size_t total;
 };
@@ -54,8 +58,9 @@ struct dmtd_ctx {
   const void* final_norm = nullptr;
   const void* lm_head = nullptr;
   std::vector<LayerW> layers;
-  std::map<std::tuple<int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late)
+  std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
   bool have_logits = false;
+  bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
 };
 
 namespace {
@@ -77,12 +82,7 @@ bool valid_config(const dmtd_config* c, std::string& why) {
   return true;
 }
 
-int rows_cap(const dmtd_config& c) {   // rows per sequence per pass
-  const int gq = c.n_q_heads / c.n_kv_heads;
-  int r = QV_MAX / gq;
-  if (r > kGemvRows) r = kGemvRows;
-  return r < 1 ? 1 : r;
-}
+int rows_cap(const dmtd_config&) { return kMaxRows; }   // rows per sequence per pass
 
 size_t weight_elems(const dmtd_config& c) {
   const size_t d = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, kd = (size_t)c.n_kv_heads * c.head_dim, ff = c.intermediate;
@@ -109,9 +109,9 @@ Ws layout(const dmtd_config& c) {
   w.attn = take(rows * qd * 4);
   w.mlp = take(rows * (size_t)c.intermediate * 4);
   w.logits = take(B * (size_t)c.vocab * 4);
-  w.part_o = take(B * c.n_kv_heads * splits * QV_MAX * hd * 4);
-  w.part_ml = take(B * c.n_kv_heads * splits * QV_MAX * 2 * 4);
-  w.att_ctr = take(B * c.n_kv_heads * 4);
+  const size_t qv_stride = (size_t)kMaxRows * (c.n_q_heads / c.n_kv_heads);
+  w.part_o = take(B * c.n_kv_heads * splits * qv_stride * hd * 4);
+  w.part_ml = take(B * c.n_kv_heads * splits * qv_stride * 2 * 4);
   w.amax = take(B * 8);
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
@@ -138,37 +138,67 @@ template <typename WT, int M, int EPI, bool NORM>
 hipError_t launch_gemv(dmtd_ctx* c, GemvArgs a) {
   // narrow outputs with long rows: the waves of a block split K
   if constexpr ((EPI == EPI_RESID || EPI == EPI_STORE) && !NORM) {
-    if (a.K >= 1024 && a.K <= 4 * GEMV_ITS * 512 && a.N <= 8192) {
-      hipLaunchKernelGGL((gemv_ksplit_kernel<WT, M, EPI>), dim3((a.N + 7) / 8), dim3(256), 0, c->stream, a);
-      return hipGetLastError();
+    if (a.K >= 1024 && a.N <= 8192) {
+      if (a.K <= 4 * 2 * 512) {
+        hipLaunchKernelGGL((gemv_ksplit_kernel<WT, M, EPI, 2, 4, 1>), dim3((a.N + 3) / 4), dim3(256), 0, c->stream, a);
+        return hipGetLastError();
+      }
+      if (a.K <= 4 * 5 * 512) {
+        hipLaunchKernelGGL((gemv_ksplit_kernel<WT, M, EPI, 5, 4, 1>), dim3((a.N + 3) / 4), dim3(256), 0, c->stream, a);
+        return hipGetLastError();
+      }
     }
   }
   const size_t lds = (size_t)M * a.K * 4;
-  auto kern = gemv_rows_kernel<WT, M, EPI, NORM>;
-  static bool configured = false;
-  if (lds > 48 * 1024 && !configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  auto kern = gemv_rows_kernel<WT, M, EPI, NORM, 5>;
+  static int occ_cache = -1;
+  static size_t occ_lds = 0;
   if (lds > 160 * 1024 - 4096) return hipErrorInvalidValue;
+  if (occ_cache < 0 || occ_lds != lds) {
+    if (lds > 48 * 1024) {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+      if (e != hipSuccess) return e;
+    }
+    int occ = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, 256, lds);
+    if (e != hipSuccess) return e;
+    occ_cache = occ < 1 ? 1 : occ;
+    occ_lds = lds;
+  }
   constexpr int RPW = (EPI == EPI_SWIGLU) ? 2 : 4;
   const int tasks = (a.N + RPW - 1) / RPW;
-  // resident blocks per CU: bounded by registers (3 blocks of 4 waves) and by the LDS the rows take
-  int per_cu = (int)((160 * 1024 - 4096) / (lds + 1024));
-  if (per_cu > 3) per_cu = 3;
-  if (per_cu < 1) per_cu = 1;
-  // every wave gets the same number of tasks (k), as far as the row count allows
-  const int waves_cap = c->num_cus * per_cu * 4;
-  const int k = (tasks + waves_cap - 1) / waves_cap;
-  int blocks = (tasks + 4 * k - 1) / (4 * k);
-  if (blocks < 1) blocks = 1;
+  int blocks = (tasks + 3) / 4;                      // one task per wave ...
+  const int cap = c->num_cus * occ_cache;            // ... unless that exceeds what is resident at once
+  if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, c->stream, a);
+  return hipGetLastError();
+}
+
+// bf16 models, 2..16 rows: the MFMA kernel (weights are read once for up to 16 rows)
+template <int EPI, bool NORM>
+hipError_t launch_gemv_mfma(dmtd_ctx* c, const GemvArgs& a, int m) {
+  const int KS = a.K / 64;
+  const int nw = (KS + kMfmaPF - 1) / kMfmaPF;
+  const int mats = EPI == EPI_SWIGLU ? 2 : 1;
+  hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF>), dim3((a.N + 15) / 16), dim3(64 * nw * mats), 0, c->stream, a, m, nw);
   return hipGetLastError();
 }
 
 template <typename WT, int EPI, bool NORM>
 hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
+  if constexpr (std::is_same<WT, bf16_t>::value && EPI != EPI_LOGITS) {
+    const int nw = (a.K / 64 + kMfmaPF - 1) / kMfmaPF;
+    if (rows >= 2 && a.K % 64 == 0 && nw * (EPI == EPI_SWIGLU ? 2 : 1) <= MFMA_MAX_WAVES) {
+      for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
+        GemvArgs g = a;
+        g.x = a.x + (size_t)m0 * a.ldx;
+        g.y = a.y + (size_t)m0 * a.ldy;
+        hipError_t e = launch_gemv_mfma<EPI, NORM>(c, g, rows - m0 < kMfmaRows ? rows - m0 : kMfmaRows);
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
+    }
+  }
   // rows are processed in groups of up to kGemvRows; each group streams the matrix once
   for (int m0 = 0; m0 < rows; m0 += kGemvRows) {
     const int m = rows - m0 < kGemvRows ? rows - m0 : kGemvRows;
@@ -192,29 +222,38 @@ template <typename WT, int HD, int QVT>
 void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
+  const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
   const WT* kc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
   const WT* vc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
   // enough splits to put about two blocks on every CU, whatever the batch
-  int ns = 2 * c->num_cus / (cf.n_kv_heads * B);
+  int ns = 2 * c->num_cus / (cf.n_kv_heads * B * n_rg);
   if (ns > ATT_MAX_SPLITS) ns = ATT_MAX_SPLITS;
   if (ns < 1) ns = 1;
-  hipLaunchKernelGGL((attn_decode_kernel<WT, HD, QVT>), dim3(ns, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv, kc, vc,
-                     (float*)(c->ws + c->o.part_o), (float*)(c->ws + c->o.part_ml), (unsigned int*)(c->ws + c->o.att_ctr),
-                     attn, qd, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, (const DevState*)(c->ws + c->o.state), sel, offset, r);
+  float* po = (float*)(c->ws + c->o.part_o);
+  float* pml = (float*)(c->ws + c->o.part_ml);
+  const DevState* st = (const DevState*)(c->ws + c->o.state);
+  hipLaunchKernelGGL((attn_decode_kernel<WT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
+                     kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, ns, kMaxRows * gq, st, sel, offset, r);
+  hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(r, cf.n_kv_heads, B), dim3(256), 0, c->stream, po, pml, attn, qd,
+                     cf.n_q_heads, cf.n_kv_heads, ns, kMaxRows * gq, st, sel, offset, r);
 }
 
+// share_kv: all rows of a sequence go through one block so that K and V are read once
+// (long contexts); otherwise rows are spread over blocks (short contexts, K/V re-reads hit in L2).
 template <typename WT>
-hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r) {
+hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r, bool share_kv) {
   const dmtd_config& cf = c->cfg;
-  const int qv = r * (cf.n_q_heads / cf.n_kv_heads);
-  if (qv > QV_MAX) return hipErrorInvalidValue;
+  const int gq = cf.n_q_heads / cf.n_kv_heads;
+  if (r > kMaxRows) return hipErrorInvalidValue;
+  const int want = share_kv ? r * gq : gq;
+  const int qvt = want <= 4 ? 4 : (want <= 8 ? 8 : 16);
   if (cf.head_dim == 128) {
-    if (qv <= 4) launch_attention_t<WT, 128, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qv <= 8) launch_attention_t<WT, 128, 8>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<WT, 128, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_t<WT, 128, 8>(c, l, qkv, attn, sel, offset, r);
     else launch_attention_t<WT, 128, 16>(c, l, qkv, attn, sel, offset, r);
   } else {
-    if (qv <= 4) launch_attention_t<WT, 64, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qv <= 8) launch_attention_t<WT, 64, 8>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<WT, 64, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_t<WT, 64, 8>(c, l, qkv, attn, sel, offset, r);
     else launch_attention_t<WT, 64, 16>(c, l, qkv, attn, sel, offset, r);
   }
   return hipGetLastError();
@@ -249,7 +288,7 @@ hipError_t run_layers(dmtd_ctx* c, int l0, int l1, float* h, int r, int sel, int
                        qkv, nqkv, w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, cf.n_q_heads,
                        cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps, st, sel, explicit_pos, r);
     // a4: split-K GQA attention + merge
-    if ((e = launch_attention<WT>(c, l, qkv, attn, sel, explicit_pos, r)) != hipSuccess) return e;
+    if ((e = launch_attention<WT>(c, l, qkv, attn, sel, explicit_pos, r, c->share_kv)) != hipSuccess) return e;
     // a5: O projection + residual
     a = GemvArgs{};
     a.W = w.o; a.x = attn; a.ldx = qd; a.y = h; a.ldy = d; a.N = d; a.K = qd;
@@ -323,12 +362,19 @@ hipError_t enqueue_step_any(dmtd_ctx* c, bool full, int r, int n_late) {
                                         : enqueue_step<bf16_t>(c, full, r, n_late);
 }
 
+// K/V bytes one layer's attention reads for the whole batch at context length ctx
+bool kv_is_large(const dmtd_ctx* c, int ctx) {
+  const size_t bytes = (size_t)c->batch * ctx * c->cfg.n_kv_heads * c->cfg.head_dim * 2 * c->elem;
+  return bytes > ((size_t)48 << 20);
+}
+
 int run_step(dmtd_ctx* c, const Step& s, int n_late) {
+  c->share_kv = kv_is_large(c, s.pos + 1);
   if (!c->cfg.use_graphs) {
     HIP_TRY(c, enqueue_step_any(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late);
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->share_kv ? 1 : 0);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -365,6 +411,7 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
   int r_last = 0;
   for (int p0 = 0; p0 < P; p0 += chunk) {
     const int r = P - p0 < chunk ? P - p0 : chunk;
+    c->share_kv = kv_is_large(c, p0 + r);
     hipLaunchKernelGGL(embed_kernel<WT>, dim3(B * r), dim3(256), 0, c->stream, (const WT*)c->embed, tokens, cf.max_seq_len,
                        st, (int)POS_EXPLICIT, p0, r, d, h);
     if ((e = run_layers<WT>(c, 0, cf.n_layers, h, r, POS_EXPLICIT, p0, add_at)) != hipSuccess) return e;
@@ -423,7 +470,7 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
       // attention for `rows` query rows per sequence ending at the newest cached position
       const int last = c->sched.n_tok - 1;
       const int r = rows <= last + 1 ? rows : 1;
-      return launch_attention<WT>(c, l, qkv, attn, (int)POS_EXPLICIT, last - r + 1, r);
+      return launch_attention<WT>(c, l, qkv, attn, (int)POS_EXPLICIT, last - r + 1, r, c->share_kv);
     }
   }
 }
@@ -499,7 +546,6 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
     std::vector<double> inv(hd / 2);
     for (size_t i = 0; i < hd / 2; ++i) inv[i] = std::pow((double)cfg->rope_theta, -2.0 * (double)i / (double)hd);
     hipError_t e = hipMemcpyAsync(c->ws + lay.inv_freq, inv.data(), inv.size() * 8, hipMemcpyHostToDevice, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.att_ctr, 0, (size_t)cfg->max_batch * cfg->n_kv_heads * 4, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)cfg->max_batch * 8, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, 256, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
@@ -671,7 +717,7 @@ int dmtd_read_kv(dmtd_ctx* c, int32_t layer, int32_t b, int32_t n_pos, float* ou
 
 int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, float* avg_us) {
   if (!c) return DMTD_EINVAL;
-  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > kGemvRows || reps < 1) {
+  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > kMaxRows || reps < 1) {
     c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
   }
   if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }

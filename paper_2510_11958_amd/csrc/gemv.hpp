@@ -57,9 +57,7 @@ __device__ __forceinline__ float wave_reduce_multi(float (&v)[V], int lane) {
 
 template <int M> struct PadRows { static constexpr int MP = M == 3 ? 4 : M; static constexpr int SH = MP == 1 ? 0 : MP == 2 ? 1 : 2; };
 
-constexpr int GEMV_ITS = 5;        // k-iterations (of 512 elements) a wave holds in registers per row
-
-template <typename WT, int M, int EPI, bool NORM>
+template <typename WT, int M, int EPI, bool NORM, int GEMV_ITS>   // GEMV_ITS: k-iterations (of 512) a wave prefetches per row
 __global__ void __launch_bounds__(256) gemv_rows_kernel(GemvArgs a) {
   extern __shared__ float4 smem4[];
   float* xs = (float*)smem4;                       // [M][K]
@@ -193,37 +191,37 @@ __global__ void __launch_bounds__(256) gemv_rows_kernel(GemvArgs a) {
   }
 }
 
-// Block = 4 waves = 8 output rows (two groups of 4); wave w takes the k-iterations
-// w, w+4, w+8, ... (up to GEMV_ITS of them, so K <= 10240).
-template <typename WT, int M, int EPI>
-__global__ void __launch_bounds__(256) gemv_ksplit_kernel(GemvArgs a) {
+// Block = NW waves = 4*RG output rows (RG groups of 4); wave w takes the k-iterations
+// w, w+NW, w+2NW, ... (ITS of them at most, so K <= NW * ITS * 512).
+template <typename WT, int M, int EPI, int ITS, int NW, int RG>
+__global__ void __launch_bounds__(64 * NW) gemv_ksplit_kernel(GemvArgs a) {
   typedef typename Elem<WT>::Raw Raw;
-  constexpr int MP = PadRows<M>::MP, V = 4 * MP, RG = 2;
+  constexpr int MP = PadRows<M>::MP, V = 4 * MP;
   constexpr int LOGV = V == 4 ? 2 : V == 8 ? 3 : 4;
-  __shared__ float red[RG][4][V];
+  __shared__ float red[RG][NW][V];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int K = a.K, N = a.N;
   const WT* __restrict__ W = (const WT*)a.W;
   const int nb0 = blockIdx.x * (4 * RG);
 
-  Raw wr[4][GEMV_ITS];
+  Raw wr[4][ITS];
   auto load_group = [&](int rg) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const WT* row = W + (size_t)min(nb0 + rg * 4 + r, N - 1) * K;
 #pragma unroll
-      for (int j = 0; j < GEMV_ITS; ++j) {
-        const int k0 = (wave + 4 * j) * 512 + lane * 8;
+      for (int j = 0; j < ITS; ++j) {
+        const int k0 = (wave + NW * j) * 512 + lane * 8;
         wr[r][j] = k0 < K ? Elem<WT>::load_raw(row + k0) : Elem<WT>::zero_raw();
       }
     }
   };
   load_group(0);
 
-  float xr[M][GEMV_ITS][8];
+  float xr[M][ITS][8];
 #pragma unroll
-  for (int j = 0; j < GEMV_ITS; ++j) {
-    const int k0 = (wave + 4 * j) * 512 + lane * 8;
+  for (int j = 0; j < ITS; ++j) {
+    const int k0 = (wave + NW * j) * 512 + lane * 8;
 #pragma unroll
     for (int m = 0; m < M; ++m) {
       float4 xa = make_float4(0, 0, 0, 0), xb = xa;
@@ -242,7 +240,7 @@ __global__ void __launch_bounds__(256) gemv_ksplit_kernel(GemvArgs a) {
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
 #pragma unroll
-    for (int j = 0; j < GEMV_ITS; ++j) {
+    for (int j = 0; j < ITS; ++j) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         float w[8];
@@ -263,7 +261,9 @@ __global__ void __launch_bounds__(256) gemv_ksplit_kernel(GemvArgs a) {
     const int rg = tid / V, idx = tid % V, r = idx >> PadRows<M>::SH, m = idx & (MP - 1);
     const int n = nb0 + rg * 4 + r;
     if (m < M && n < N) {
-      const float s = (red[rg][0][idx] + red[rg][1][idx]) + (red[rg][2][idx] + red[rg][3][idx]);
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) s += red[rg][w][idx];
       float* dst = a.y + (size_t)m * a.ldy + n;
       if (EPI == EPI_RESID) *dst += s; else *dst = s;
     }

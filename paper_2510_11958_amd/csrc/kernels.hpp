@@ -231,4 +231,5 @@ __global__ void __launch_bounds__(64) qk_norm_rope_append_kernel(
 }  // namespace dmtd
 
 #include "gemv.hpp"
+#include "gemv_mfma.hpp"
 #include "attention.hpp"
