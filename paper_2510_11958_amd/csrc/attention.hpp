@@ -207,9 +207,9 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
 
 // Merge the splits' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
 // f_s = exp(m_s - max_s m_s), splits taken in order.  One block per (row, KV head, sequence).
-template <int HD>
+template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection)
 __global__ void __launch_bounds__(256) attn_merge_kernel(
-    const float* __restrict__ part_o, const float* __restrict__ part_ml, float* __restrict__ out, int ldo,
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, int ldo,
     int nh, int nkv, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
   const int i = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
@@ -247,7 +247,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(
       const float v = po[(size_t)s2 * qv_stride * HD];
       o += (f == 0.f) ? 0.f : f * v;      // splits without visible keys hold stale partials: weight 0, value ignored
     }
-    out[(size_t)(b * r_total + i) * ldo + (size_t)(g * GQ + j) * HD + d] = o * inv_l[j];
+    out[(size_t)(b * r_total + i) * ldo + (size_t)(g * GQ + j) * HD + d] = Elem<OT>::from_f32(o * inv_l[j]);
   }
 }
 

@@ -1,5 +1,11 @@
 // C ABI of the DMTD decode path (see include/dmtd.h): context, workspace layout, step
 // assembly, hipGraph capture/replay and the host-visible calls.
+//
+// Two kernel paths share the step assembly:
+//  - bf16 models ("packed" path): weights repacked once into MFMA operand order, all
+//    projections through the MFMA weight-streaming kernel, activations handed from kernel
+//    to kernel as packed bf16 rows plus partial sums of squares for the next RMSNorm;
+//  - the fp32 parity model: FMA weight-streaming kernels with the norm computed in-kernel.
 #include "../../include/dmtd.h"
 
 #include <hip/hip_runtime.h>
@@ -10,7 +16,6 @@
 #include <map>
 #include <string>
 #include <tuple>
-#include <type_traits>
 #include <vector>
 
 #include "kernels.hpp"
@@ -21,23 +26,36 @@ using namespace dmtd;
 namespace {
 
 constexpr int kMaxTau = 64;          // steps per decode call (size of the emitted-token buffer)
-constexpr int kGemvRows = 4;         // activation rows per weight-streaming pass
-constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
+constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming pass
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
+constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
 constexpr int kMfmaRows = 16;        // activation rows per MFMA weight-streaming pass
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 
 thread_local std::string g_create_error;
 
-struct LayerW {
+struct LayerW {   // tensors of one layer inside the caller's blob
   const void *attn_norm, *q, *k, *v, *q_norm, *k_norm, *o, *mlp_norm, *gate, *up, *down;
+};
+struct LayerSw {  // the layer's matrices in MFMA operand order (workspace; bf16 models only)
+  const bf16_t *qkv, *o, *gate, *up, *down;
 };
 
 struct Ws {   // device workspace carve-up (byte offsets)
   size_t kv, kv_layer_stride, kv_v_off;
   size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, amax;
-  size_t tokens, emitted, forced, state, inv_freq, scratch_f32;
+  size_t tokens, emitted, forced, state, inv_freq;
+  size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
   size_t total;
+};
+
+// Activation rows in flight between kernels.  On the packed path xb holds bf16(h * gain of
+// the norm that reads the rows next) and ssp the partial sums of h^2 (n_parts of them per row).
+struct Rows {
+  float* h;
+  bf16_t* xb;
+  float* ssp;
+  int n_parts;
 };
 
 }  // namespace
@@ -48,18 +66,20 @@ struct dmtd_ctx {
   std::string err;
   hipStream_t stream = nullptr;
   int elem = 2;
+  bool packed = false;        // bf16 model: MFMA path
   int num_cus = 256;
   int batch = 0;              // batch of the current sequence set (after prefill)
-  int max_rows = 0;           // rows per sequence a pass may carry
+  int ssp_ld = 0;             // row capacity of the sum-of-squares buffers
   const char* wbase = nullptr;
   char* ws = nullptr;
   Ws o{};
   const void* embed = nullptr;
   const void* final_norm = nullptr;
   const void* lm_head = nullptr;
+  const bf16_t* lm_head_sw = nullptr;
   std::vector<LayerW> layers;
+  std::vector<LayerSw> sw;
   std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
-  bool have_logits = false;
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
 };
 
@@ -77,12 +97,13 @@ bool valid_config(const dmtd_config* c, std::string& why) {
   if (c->n_q_heads % c->n_kv_heads) { why = "n_q_heads must be a multiple of n_kv_heads"; return false; }
   if (c->n_q_heads / c->n_kv_heads > QV_MAX) { why = "too many query heads per KV head"; return false; }
   if (c->dtype != DMTD_DTYPE_F32 && c->dtype != DMTD_DTYPE_BF16) { why = "unknown dtype"; return false; }
+  if (c->dtype == DMTD_DTYPE_BF16 && (c->hidden % 64 || c->intermediate % 64)) {
+    why = "bf16 models need hidden and intermediate to be multiples of 64"; return false;
+  }
   if (c->max_batch < 1 || c->max_seq_len < 2) { why = "max_batch >= 1 and max_seq_len >= 2 required"; return false; }
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) { why = "rms_eps and rope_theta must be positive"; return false; }
   return true;
 }
-
-int rows_cap(const dmtd_config&) { return kMaxRows; }   // rows per sequence per pass
 
 size_t weight_elems(const dmtd_config& c) {
   const size_t d = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, kd = (size_t)c.n_kv_heads * c.head_dim, ff = c.intermediate;
@@ -90,13 +111,18 @@ size_t weight_elems(const dmtd_config& c) {
   return (size_t)c.vocab * d + c.n_layers * per_layer + d + (c.tied_embeddings ? 0 : (size_t)c.vocab * d);
 }
 
+size_t swizzled_layer_elems(const dmtd_config& c) {
+  const size_t d = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, ff = c.intermediate;
+  const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  return swizzled_elems(nqkv, d) + swizzled_elems(d, qd) + 2 * swizzled_elems(ff, d) + swizzled_elems(d, ff);
+}
+
 Ws layout(const dmtd_config& c) {
   Ws w{};
   const size_t e = c.dtype == DMTD_DTYPE_F32 ? 4 : 2;
   const size_t B = c.max_batch, S = c.max_seq_len, d = c.hidden, hd = c.head_dim;
   const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * hd, qd = (size_t)c.n_q_heads * hd;
-  const size_t rows = B * rows_cap(c);
-  const size_t splits = ATT_MAX_SPLITS;
+  const size_t rows = B * kMaxRows;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t kv_one = B * c.n_kv_heads * S * hd * e;       // K (or V) of one layer
@@ -106,19 +132,26 @@ Ws layout(const dmtd_config& c) {
   w.h = take(rows * d * 4);
   w.h_late = take(B * d * 4);
   w.qkv = take(rows * nqkv * 4);
-  w.attn = take(rows * qd * 4);
-  w.mlp = take(rows * (size_t)c.intermediate * 4);
+  w.attn = take(rows * qd * 4);                       // fp32 path: fp32 rows; packed path: bf16 rows
+  w.mlp = take(rows * (size_t)c.intermediate * 4);    // likewise
   w.logits = take(B * (size_t)c.vocab * 4);
   const size_t qv_stride = (size_t)kMaxRows * (c.n_q_heads / c.n_kv_heads);
-  w.part_o = take(B * c.n_kv_heads * splits * qv_stride * hd * 4);
-  w.part_ml = take(B * c.n_kv_heads * splits * qv_stride * 2 * 4);
-  w.amax = take(B * 8);
+  w.part_o = take(B * c.n_kv_heads * ATT_MAX_SPLITS * qv_stride * hd * 4);
+  w.part_ml = take(B * c.n_kv_heads * ATT_MAX_SPLITS * qv_stride * 2 * 4);
+  w.amax = take((size_t)AMAX_CELLS * B * 8);
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
   w.forced = take((size_t)kMaxTau * B * 4);
   w.state = take(256);
   w.inv_freq = take((hd / 2) * 8);
-  w.scratch_f32 = take(256);
+  if (c.dtype == DMTD_DTYPE_BF16) {
+    const size_t parts = (d + 15) / 16;
+    w.xb = take(rows * d * 2);
+    w.xb_late = take(B * d * 2);
+    w.ssp = take(parts * rows * 4);
+    w.ssp_late = take(parts * rows * 4);
+    w.wsw = take((swizzled_layer_elems(c) * c.n_layers + swizzled_elems(c.vocab, d)) * 2);
+  }
   w.total = off;
   return w;
 }
@@ -132,7 +165,13 @@ Ws layout(const dmtd_config& c) {
     }                                                                                   \
   } while (0)
 
-// ------------------------------------------------------------------ launch helpers
+DevState* dev_state(dmtd_ctx* c) { return (DevState*)(c->ws + c->o.state); }
+int* dev_tokens(dmtd_ctx* c) { return (int*)(c->ws + c->o.tokens); }
+const void* norm_gain_for_layer(const dmtd_ctx* c, int l) {   // gain of the norm that opens layer l (the final norm after the last)
+  return l < c->cfg.n_layers ? c->layers[l].attn_norm : c->final_norm;
+}
+
+// ------------------------------------------------------- fp32 path: FMA weight streaming
 
 template <typename WT, int M, int EPI, bool NORM>
 hipError_t launch_gemv(dmtd_ctx* c, GemvArgs a) {
@@ -174,31 +213,8 @@ hipError_t launch_gemv(dmtd_ctx* c, GemvArgs a) {
   return hipGetLastError();
 }
 
-// bf16 models, 2..16 rows: the MFMA kernel (weights are read once for up to 16 rows)
-template <int EPI, bool NORM>
-hipError_t launch_gemv_mfma(dmtd_ctx* c, const GemvArgs& a, int m) {
-  const int KS = a.K / 64;
-  const int nw = (KS + kMfmaPF - 1) / kMfmaPF;
-  const int mats = EPI == EPI_SWIGLU ? 2 : 1;
-  hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF>), dim3((a.N + 15) / 16), dim3(64 * nw * mats), 0, c->stream, a, m, nw);
-  return hipGetLastError();
-}
-
 template <typename WT, int EPI, bool NORM>
 hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
-  if constexpr (std::is_same<WT, bf16_t>::value && EPI != EPI_LOGITS) {
-    const int nw = (a.K / 64 + kMfmaPF - 1) / kMfmaPF;
-    if (rows >= 2 && a.K % 64 == 0 && nw * (EPI == EPI_SWIGLU ? 2 : 1) <= MFMA_MAX_WAVES) {
-      for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
-        GemvArgs g = a;
-        g.x = a.x + (size_t)m0 * a.ldx;
-        g.y = a.y + (size_t)m0 * a.ldy;
-        hipError_t e = launch_gemv_mfma<EPI, NORM>(c, g, rows - m0 < kMfmaRows ? rows - m0 : kMfmaRows);
-        if (e != hipSuccess) return e;
-      }
-      return hipSuccess;
-    }
-  }
   // rows are processed in groups of up to kGemvRows; each group streams the matrix once
   for (int m0 = 0; m0 < rows; m0 += kGemvRows) {
     const int m = rows - m0 < kGemvRows ? rows - m0 : kGemvRows;
@@ -218,148 +234,270 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
   return hipSuccess;
 }
 
-template <typename WT, int HD, int QVT>
-void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r) {
+// ---------------------------------------------------- packed path: MFMA weight streaming
+
+// nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4}) that lets a wave
+// hold its k-range in one round of kMfmaPF k-steps, else the largest with several rounds.
+// Rows beyond 16 go in further launches (each streams the matrix again).
+template <int EPI, bool NORM>
+hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
+  const int KS = a.K / 64;
+  constexpr int MATS = EPI == EPI_SWIGLU ? 2 : 1;
+  const int nw_max = EPI == EPI_SWIGLU ? 4 : 8;
+  int nw = 2;
+  while (nw < nw_max && (KS + nw - 1) / nw > kMfmaPF) nw *= 2;
+  const dim3 grid((a.N + 15) / 16);
+  for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
+    MfmaArgs g = a;
+    g.M = rows - m0 < kMfmaRows ? rows - m0 : kMfmaRows;
+    g.xb = a.xb + (size_t)m0 * a.ldxb;
+    if (a.ssp) g.ssp = a.ssp + m0;
+    if (a.y) g.y = a.y + (size_t)m0 * a.ldy;
+    if (a.yb) g.yb = a.yb + (size_t)m0 * a.ldyb;
+    if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
+    if (a.amax) g.amax = a.amax + m0;
+    // B operands through LDS when the packed rows fit comfortably (frees registers: more waves per CU)
+    const size_t lds = (size_t)g.M * (a.K + 8) * 2;
+    const bool blds = lds <= 60 * 1024;
+#define DMTD_LAUNCH_MFMA(NWT_)                                                                                              \
+    do {                                                                                                                    \
+      if (blds) hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF, NWT_, true>), grid, dim3(64 * NWT_), lds, c->stream, g); \
+      else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);       \
+    } while (0)
+    if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
+    else if (nw == 4) DMTD_LAUNCH_MFMA(4 * MATS);
+    else {
+      if constexpr (EPI != EPI_SWIGLU) DMTD_LAUNCH_MFMA(8);
+    }
+#undef DMTD_LAUNCH_MFMA
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- attention
+
+template <typename CT, typename OT, int HD, int QVT>
+void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
   const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
-  const WT* kc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
-  const WT* vc = (const WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  const CT* kc = (const CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  const CT* vc = (const CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
   // enough splits to put about two blocks on every CU, whatever the batch
   int ns = 2 * c->num_cus / (cf.n_kv_heads * B * n_rg);
   if (ns > ATT_MAX_SPLITS) ns = ATT_MAX_SPLITS;
   if (ns < 1) ns = 1;
   float* po = (float*)(c->ws + c->o.part_o);
   float* pml = (float*)(c->ws + c->o.part_ml);
-  const DevState* st = (const DevState*)(c->ws + c->o.state);
-  hipLaunchKernelGGL((attn_decode_kernel<WT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
+  const DevState* st = dev_state(c);
+  hipLaunchKernelGGL((attn_decode_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, ns, kMaxRows * gq, st, sel, offset, r);
-  hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3(r, cf.n_kv_heads, B), dim3(256), 0, c->stream, po, pml, attn, qd,
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_kv_heads, B), dim3(256), 0, c->stream, po, pml, attn, qd,
                      cf.n_q_heads, cf.n_kv_heads, ns, kMaxRows * gq, st, sel, offset, r);
 }
 
 // share_kv: all rows of a sequence go through one block so that K and V are read once
 // (long contexts); otherwise rows are spread over blocks (short contexts, K/V re-reads hit in L2).
-template <typename WT>
-hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, float* attn, int sel, int offset, int r, bool share_kv) {
+template <typename CT, typename OT>
+hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
   const dmtd_config& cf = c->cfg;
   const int gq = cf.n_q_heads / cf.n_kv_heads;
   if (r > kMaxRows) return hipErrorInvalidValue;
-  const int want = share_kv ? r * gq : gq;
+  const int want = c->share_kv ? r * gq : gq;
   const int qvt = want <= 4 ? 4 : (want <= 8 ? 8 : 16);
   if (cf.head_dim == 128) {
-    if (qvt == 4) launch_attention_t<WT, 128, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_t<WT, 128, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_t<WT, 128, 16>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<CT, OT, 128, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_t<CT, OT, 128, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_t<CT, OT, 128, 16>(c, l, qkv, attn, sel, offset, r);
   } else {
-    if (qvt == 4) launch_attention_t<WT, 64, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_t<WT, 64, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_t<WT, 64, 16>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<CT, OT, 64, 4>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_t<CT, OT, 64, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_t<CT, OT, 64, 16>(c, l, qkv, attn, sel, offset, r);
   }
   return hipGetLastError();
 }
 
-template <typename WT>
-hipError_t run_layers(dmtd_ctx* c, int l0, int l1, float* h, int r, int sel, int explicit_pos,
-                      int add_embed_at /* layer before which the embedding is re-added, or -1 */) {
+// ---------------------------------------------------------------- the steps of a pass
+
+// a1: rows <- embeddings of the tokens at the rows' positions (next reader: the norm of layer next_layer)
+hipError_t embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int next_layer) {
   const dmtd_config& cf = c->cfg;
-  const int B = c->batch, rows = B * r, d = cf.hidden, hd = cf.head_dim;
+  const int rows = c->batch * r;
+  if (c->packed) {
+    hipLaunchKernelGGL(embed_pack_kernel, dim3(rows), dim3(256), 0, c->stream, (const bf16_t*)c->embed, dev_tokens(c),
+                       cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h, (const bf16_t*)norm_gain_for_layer(c, next_layer),
+                       R.xb, R.ssp);
+    R.n_parts = 1;
+  } else {
+    hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, c->stream, (const float*)c->embed, dev_tokens(c),
+                       cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h);
+  }
+  return hipGetLastError();
+}
+
+// literal Eq. 4 during prefill: rows += their embeddings, before layer next_layer
+hipError_t add_embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int next_layer) {
+  const dmtd_config& cf = c->cfg;
+  const int rows = c->batch * r;
+  if (c->packed) {
+    hipLaunchKernelGGL(add_embed_pack_kernel, dim3(rows), dim3(256), 0, c->stream, R.h, (const bf16_t*)c->embed, dev_tokens(c),
+                       cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, (const bf16_t*)norm_gain_for_layer(c, next_layer),
+                       R.xb, R.ssp);
+    R.n_parts = 1;
+  } else {
+    hipLaunchKernelGGL(add_embed_rows_kernel<float>, dim3(rows), dim3(256), 0, c->stream, R.h, (const float*)c->embed,
+                       dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden);
+  }
+  return hipGetLastError();
+}
+
+// a8: only each sequence's newest row continues (Sec. 2.2); under the literal Eq. 4 reading its embedding is added
+hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int add_embed, int sel, int offset, int next_layer) {
+  const dmtd_config& cf = c->cfg;
+  if (c->packed) {
+    hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden, add_embed,
+                       (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset,
+                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.ssp);
+    dst.n_parts = 1;
+  } else {
+    hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden,
+                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset);
+  }
+  return hipGetLastError();
+}
+
+// a2..a7: one transformer block over r rows per sequence at positions base + offset + i
+hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
+  const dmtd_config& cf = c->cfg;
+  const int rows = c->batch * r, d = cf.hidden, hd = cf.head_dim, ff = cf.intermediate;
   const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * hd, qd = cf.n_q_heads * hd;
   float* qkv = (float*)(c->ws + c->o.qkv);
+  const LayerW& w = c->layers[l];
+  char* kc = c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride;
+  char* vc = kc + c->o.kv_v_off;
+  const double* inv_freq = (const double*)(c->ws + c->o.inv_freq);
+  const dim3 rope_grid(cf.n_q_heads + 2 * cf.n_kv_heads, rows);
+  hipError_t e;
+  if (c->packed) {
+    const LayerSw& s = c->sw[l];
+    bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);
+    bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);
+    const int tiles_d = (d + 15) / 16;
+    MfmaArgs a{};
+    // a2: RMSNorm + fused QKV projection
+    a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
+    a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
+    if ((e = launch_mfma<EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
+    // a3: QK-RMSNorm + RoPE + KV append
+    hipLaunchKernelGGL(qk_norm_rope_append_kernel<bf16_t>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
+                       inv_freq, (bf16_t*)kc, (bf16_t*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
+                       dev_state(c), sel, offset, r);
+    // a4: split-K GQA attention + merge (output packed for the O projection)
+    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
+    // a5: O projection + residual; emits the MLP norm's input
+    a = MfmaArgs{};
+    a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+    a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
+    if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+    R.n_parts = tiles_d;
+    // a6: RMSNorm + gate/up + SwiGLU
+    a = MfmaArgs{};
+    a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts;
+    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.yb = ub; a.ldyb = ff;
+    if ((e = launch_mfma<EPI_SWIGLU, true>(c, a, rows)) != hipSuccess) return e;
+    // a7: down projection + residual; emits the next layer's (or the final) norm input
+    a = MfmaArgs{};
+    a.W = s.down; a.xb = ub; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+    a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
+    if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+    R.n_parts = tiles_d;
+    return hipSuccess;
+  }
   float* attn = (float*)(c->ws + c->o.attn);
   float* mlp = (float*)(c->ws + c->o.mlp);
-  const DevState* st = (const DevState*)(c->ws + c->o.state);
-  const int* tokens = (const int*)(c->ws + c->o.tokens);
+  GemvArgs a{};
+  a.eps = cf.rms_eps;
+  // a2: RMSNorm + fused QKV projection (q, k, v are contiguous in the blob)
+  a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
+  if ((e = gemv_rows<float, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
+  // a3: QK-RMSNorm + RoPE + KV append
+  hipLaunchKernelGGL(qk_norm_rope_append_kernel<float>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
+                     inv_freq, (float*)kc, (float*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
+                     dev_state(c), sel, offset, r);
+  // a4: split-K GQA attention + merge
+  if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
+  // a5: O projection + residual
+  a = GemvArgs{};
+  a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
+  if ((e = gemv_rows<float, EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+  // a6: RMSNorm + gate/up + SwiGLU
+  a = GemvArgs{};
+  a.eps = cf.rms_eps;
+  a.W = w.gate; a.W2 = w.up; a.gain = w.mlp_norm; a.x = R.h; a.ldx = d; a.y = mlp; a.ldy = ff; a.N = ff; a.K = d;
+  if ((e = gemv_rows<float, EPI_SWIGLU, true>(c, a, rows)) != hipSuccess) return e;
+  // a7: down projection + residual
+  a = GemvArgs{};
+  a.W = w.down; a.x = mlp; a.ldx = ff; a.y = R.h; a.ldy = d; a.N = d; a.K = ff;
+  return gemv_rows<float, EPI_RESID, false>(c, a, rows);
+}
+
+// a9: final RMSNorm + LM head + greedy selection for one row per sequence; then the step's bookkeeping
+hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int n_rows) {
+  const dmtd_config& cf = c->cfg;
+  unsigned long long* amax = (unsigned long long*)(c->ws + c->o.amax);
   hipError_t e;
-  for (int l = l0; l < l1; ++l) {
-    const LayerW& w = c->layers[l];
-    if (l == add_embed_at)
-      hipLaunchKernelGGL(add_embed_rows_kernel<WT>, dim3(rows), dim3(256), 0, c->stream, h, (const WT*)c->embed, tokens,
-                         cf.max_seq_len, st, sel, explicit_pos, r, d);
-    WT* kc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
-    WT* vc = (WT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  if (c->packed) {
+    MfmaArgs a{};
+    a.W = c->lm_head_sw; a.xb = R.xb; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
+    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
+    a.amax = amax; a.amax_ld = cf.max_batch;
+    e = launch_mfma<EPI_LOGITS, true>(c, a, n_rows);
+  } else {
     GemvArgs a{};
     a.eps = cf.rms_eps;
-    // a2: RMSNorm + fused QKV projection (q, k, v are contiguous in the blob)
-    a.W = w.q; a.gain = w.attn_norm; a.x = h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
-    if ((e = gemv_rows<WT, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
-    // a3: QK-RMSNorm + RoPE + KV append
-    hipLaunchKernelGGL(qk_norm_rope_append_kernel<WT>, dim3(cf.n_q_heads + 2 * cf.n_kv_heads, rows), dim3(64), 0, c->stream,
-                       qkv, nqkv, w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, cf.n_q_heads,
-                       cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps, st, sel, explicit_pos, r);
-    // a4: split-K GQA attention + merge
-    if ((e = launch_attention<WT>(c, l, qkv, attn, sel, explicit_pos, r, c->share_kv)) != hipSuccess) return e;
-    // a5: O projection + residual
-    a = GemvArgs{};
-    a.W = w.o; a.x = attn; a.ldx = qd; a.y = h; a.ldy = d; a.N = d; a.K = qd;
-    if ((e = gemv_rows<WT, EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
-    // a6: RMSNorm + gate/up + SwiGLU
-    a = GemvArgs{};
-    a.eps = cf.rms_eps;
-    a.W = w.gate; a.W2 = w.up; a.gain = w.mlp_norm; a.x = h; a.ldx = d; a.y = mlp; a.ldy = cf.intermediate;
-    a.N = cf.intermediate; a.K = d;
-    if ((e = gemv_rows<WT, EPI_SWIGLU, true>(c, a, rows)) != hipSuccess) return e;
-    // a7: down projection + residual
-    a = GemvArgs{};
-    a.W = w.down; a.x = mlp; a.ldx = cf.intermediate; a.y = h; a.ldy = d; a.N = d; a.K = cf.intermediate;
-    if ((e = gemv_rows<WT, EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+    a.W = c->lm_head; a.gain = c->final_norm; a.x = R.h; a.ldx = cf.hidden;
+    a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab; a.N = cf.vocab; a.K = cf.hidden;
+    a.amax = amax;
+    e = gemv_rows<float, EPI_LOGITS, true>(c, a, n_rows);
   }
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
+                     dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens);
   return hipGetLastError();
 }
 
-// a9: final RMSNorm + LM head + greedy argmax for the batch rows in h_late; then advance the device state
-template <typename WT>
-hipError_t run_head(dmtd_ctx* c, const float* h_rows, int full) {
-  const dmtd_config& cf = c->cfg;
-  GemvArgs a{};
-  a.eps = cf.rms_eps;
-  a.W = c->lm_head; a.gain = c->final_norm; a.x = h_rows; a.ldx = cf.hidden;
-  a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab; a.N = cf.vocab; a.K = cf.hidden;
-  a.amax = (unsigned long long*)(c->ws + c->o.amax);
-  hipError_t e = gemv_rows<WT, EPI_LOGITS, true>(c, a, c->batch);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state),
-                     (unsigned long long*)(c->ws + c->o.amax), (int*)(c->ws + c->o.tokens), (int*)(c->ws + c->o.emitted),
-                     cf.max_seq_len, c->batch, full, 1);
-  return hipGetLastError();
+Rows front_rows(dmtd_ctx* c) {
+  return Rows{(float*)(c->ws + c->o.h), (bf16_t*)(c->ws + c->o.xb), (float*)(c->ws + c->o.ssp), 1};
+}
+Rows late_rows(dmtd_ctx* c) {
+  return Rows{(float*)(c->ws + c->o.h_late), (bf16_t*)(c->ws + c->o.xb_late), (float*)(c->ws + c->o.ssp_late), 1};
 }
 
 // One decode step (Sec. 2.2).  Full: embed the pending rows and the newest row, run the front
 // layers on all of them, keep the newest row, run the late layers on it.  Late: embed the
 // newest token and run the late layers only (Eq. 4, m = 0).
-template <typename WT>
 hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
   const dmtd_config& cf = c->cfg;
-  const int B = c->batch, d = cf.hidden, F = cf.n_layers - n_late;
-  float* h = (float*)(c->ws + c->o.h);
-  float* h_late = (float*)(c->ws + c->o.h_late);
-  const DevState* st = (const DevState*)(c->ws + c->o.state);
-  const int* tokens = (const int*)(c->ws + c->o.tokens);
+  const int F = cf.n_layers - n_late;
+  Rows front = front_rows(c), late = late_rows(c);
   hipError_t e;
   if (full) {
     // the pending rows are causal among themselves, so groups of rows may pass the front
     // layers one after another (each group streams those layers' weights once)
     int c0 = 0, rc = 0;
     for (; c0 < r; c0 += rc) {
-      rc = r - c0 < c->max_rows ? r - c0 : c->max_rows;
-      hipLaunchKernelGGL(embed_kernel<WT>, dim3(B * rc), dim3(256), 0, c->stream, (const WT*)c->embed, tokens,
-                         cf.max_seq_len, st, (int)POS_NFRONT, c0, rc, d, h);
-      if ((e = run_layers<WT>(c, 0, F, h, rc, POS_NFRONT, c0, -1)) != hipSuccess) return e;
+      rc = r - c0 < kMaxRows ? r - c0 : kMaxRows;
+      if ((e = embed_rows(c, front, POS_NFRONT, c0, rc, 0)) != hipSuccess) return e;
+      for (int l = 0; l < F; ++l)
+        if ((e = run_layer(c, l, front, rc, POS_NFRONT, c0)) != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(take_last_rows_kernel<WT>, dim3(B), dim3(256), 0, c->stream, h, h_late, rc, d,
-                       cf.full_pos_add_embed ? 1 : 0, (const WT*)c->embed, tokens, cf.max_seq_len, st, (int)POS_NFRONT,
-                       c0 - rc);
+    if ((e = take_last_rows(c, front, late, rc, cf.full_pos_add_embed ? 1 : 0, POS_NFRONT, c0 - rc, F)) != hipSuccess) return e;
   } else {
-    hipLaunchKernelGGL(embed_kernel<WT>, dim3(B), dim3(256), 0, c->stream, (const WT*)c->embed, tokens, cf.max_seq_len, st,
-                       (int)POS_NTOK, 0, 1, d, h_late);
+    if ((e = embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
   }
-  if ((e = run_layers<WT>(c, F, cf.n_layers, h_late, 1, POS_NTOK, 0, -1)) != hipSuccess) return e;
-  return run_head<WT>(c, h_late, full ? 1 : 0);
-}
-
-hipError_t enqueue_step_any(dmtd_ctx* c, bool full, int r, int n_late) {
-  return c->cfg.dtype == DMTD_DTYPE_F32 ? enqueue_step<float>(c, full, r, n_late)
-                                        : enqueue_step<bf16_t>(c, full, r, n_late);
+  for (int l = F; l < cf.n_layers; ++l)
+    if ((e = run_layer(c, l, late, 1, POS_NTOK, 0)) != hipSuccess) return e;
+  return run_head(c, late, full ? 1 : 0, 1, c->batch);
 }
 
 // K/V bytes one layer's attention reads for the whole batch at context length ctx
@@ -371,7 +509,7 @@ bool kv_is_large(const dmtd_ctx* c, int ctx) {
 int run_step(dmtd_ctx* c, const Step& s, int n_late) {
   c->share_kv = kv_is_large(c, s.pos + 1);
   if (!c->cfg.use_graphs) {
-    HIP_TRY(c, enqueue_step_any(c, s.full, s.rows, n_late));
+    HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
   const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->share_kv ? 1 : 0);
@@ -379,7 +517,7 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
     HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-    hipError_t e = enqueue_step_any(c, s.full, s.rows, n_late);
+    hipError_t e = enqueue_step(c, s.full, s.rows, n_late);
     hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
     if (e != hipSuccess || e2 != hipSuccess) {
       if (graph) (void)hipGraphDestroy(graph);
@@ -396,82 +534,89 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
   return DMTD_OK;
 }
 
-template <typename WT>
+// Prefill (Sec. 2.2): all prompt positions through all layers, in chunks of rows
 hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
   const dmtd_config& cf = c->cfg;
-  const int B = c->batch, d = cf.hidden;
-  float* h = (float*)(c->ws + c->o.h);
-  float* h_late = (float*)(c->ws + c->o.h_late);
-  DevState* st = (DevState*)(c->ws + c->o.state);
-  const int* tokens = (const int*)(c->ws + c->o.tokens);
-  const int chunk = c->max_rows < kPrefillChunk ? c->max_rows : kPrefillChunk;
+  Rows front = front_rows(c), late = late_rows(c);
   const int add_at = cf.full_pos_add_embed ? cf.n_layers - n_late : -1;
   hipError_t e;
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, st, P - 1, P - 1);
-  int r_last = 0;
-  for (int p0 = 0; p0 < P; p0 += chunk) {
-    const int r = P - p0 < chunk ? P - p0 : chunk;
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, dev_state(c), P - 1, P - 1);
+  int r_last = 0, p_last = 0;
+  for (int p0 = 0; p0 < P; p0 += kPrefillChunk) {
+    const int r = P - p0 < kPrefillChunk ? P - p0 : kPrefillChunk;
     c->share_kv = kv_is_large(c, p0 + r);
-    hipLaunchKernelGGL(embed_kernel<WT>, dim3(B * r), dim3(256), 0, c->stream, (const WT*)c->embed, tokens, cf.max_seq_len,
-                       st, (int)POS_EXPLICIT, p0, r, d, h);
-    if ((e = run_layers<WT>(c, 0, cf.n_layers, h, r, POS_EXPLICIT, p0, add_at)) != hipSuccess) return e;
-    r_last = r;
+    if ((e = embed_rows(c, front, POS_EXPLICIT, p0, r, 0)) != hipSuccess) return e;
+    for (int l = 0; l < cf.n_layers; ++l) {
+      if (l == add_at && (e = add_embed_rows(c, front, POS_EXPLICIT, p0, r, l)) != hipSuccess) return e;
+      if ((e = run_layer(c, l, front, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
+    }
+    r_last = r; p_last = p0;
   }
-  hipLaunchKernelGGL(take_last_rows_kernel<WT>, dim3(B), dim3(256), 0, c->stream, h, h_late, r_last, d, 0,
-                     (const WT*)c->embed, tokens, cf.max_seq_len, st, (int)POS_EXPLICIT, 0);
-  return run_head<WT>(c, h_late, 1);   // state goes from P-1 to n_tok = n_front = P
+  if ((e = take_last_rows(c, front, late, r_last, 0, POS_EXPLICIT, p_last, cf.n_layers)) != hipSuccess) return e;
+  return run_head(c, late, 1, 1, c->batch);   // state goes from P-1 to n_tok = n_front = P
 }
 
 // One launch of one kernel kind on layer l, for dmtd_time_kernel.  Outputs go to scratch
-// buffers only: the QKV/attention/MLP activations, the residual scratch h (never h_late,
-// never the caches, the token history or the scheduler state).
-template <typename WT>
+// buffers only (never the late rows, the caches, the token history or the scheduler state).
 hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
   const dmtd_config& cf = c->cfg;
-  const int d = cf.hidden, hd = cf.head_dim;
+  const int d = cf.hidden, hd = cf.head_dim, ff = cf.intermediate;
   const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * hd, qd = cf.n_q_heads * hd;
-  float* h = (float*)(c->ws + c->o.h);
+  Rows R = front_rows(c);
   float* qkv = (float*)(c->ws + c->o.qkv);
+  const LayerW& w = c->layers[l];
+  if (kind == DMTD_K_ATTN) {
+    // attention for `rows` query rows per sequence ending at the newest cached position
+    const int last = c->sched.n_tok - 1;
+    const int r = rows <= last + 1 ? rows : 1;
+    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
+    return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
+  }
+  if (kind == DMTD_K_LMHEAD) {
+    R.n_parts = 1;
+    return run_head(c, R, 0, 0, rows);     // the real LM-head kernel; keys cleared, no token or state side effects
+  }
+  if (c->packed) {
+    const LayerSw& s = c->sw[l];
+    bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);
+    bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);
+    MfmaArgs a{};
+    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps;
+    switch (kind) {
+      case DMTD_K_QKV:
+        a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = 1; a.y = qkv; a.ldy = nqkv;
+        return launch_mfma<EPI_STORE, true>(c, a, rows);
+      case DMTD_K_OPROJ:
+        a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+        a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp;
+        return launch_mfma<EPI_RESID, false>(c, a, rows);
+      case DMTD_K_GATEUP:
+        a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = (d + 15) / 16;
+        a.yb = ub; a.ldyb = ff;
+        return launch_mfma<EPI_SWIGLU, true>(c, a, rows);
+      default:
+        a.W = s.down; a.xb = ub; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+        a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp;
+        return launch_mfma<EPI_RESID, false>(c, a, rows);
+    }
+  }
   float* attn = (float*)(c->ws + c->o.attn);
   float* mlp = (float*)(c->ws + c->o.mlp);
-  const LayerW& w = c->layers[l];
   GemvArgs a{};
   a.eps = cf.rms_eps;
   switch (kind) {
     case DMTD_K_QKV:
-      a.W = w.q; a.gain = w.attn_norm; a.x = h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
-      return gemv_rows<WT, EPI_STORE, true>(c, a, rows);
+      a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
+      return gemv_rows<float, EPI_STORE, true>(c, a, rows);
     case DMTD_K_OPROJ:
-      a.W = w.o; a.x = attn; a.ldx = qd; a.y = h; a.ldy = d; a.N = d; a.K = qd;
-      return gemv_rows<WT, EPI_RESID, false>(c, a, rows);
+      a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
+      return gemv_rows<float, EPI_RESID, false>(c, a, rows);
     case DMTD_K_GATEUP:
-      a.W = w.gate; a.W2 = w.up; a.gain = w.mlp_norm; a.x = h; a.ldx = d; a.y = mlp; a.ldy = cf.intermediate;
-      a.N = cf.intermediate; a.K = d;
-      return gemv_rows<WT, EPI_SWIGLU, true>(c, a, rows);
-    case DMTD_K_DOWN:
-      a.W = w.down; a.x = mlp; a.ldx = cf.intermediate; a.y = h; a.ldy = d; a.N = d; a.K = cf.intermediate;
-      return gemv_rows<WT, EPI_RESID, false>(c, a, rows);
-    case DMTD_K_LMHEAD: {
-      // the real LM-head kernel (logits + argmax); a null token history suppresses its token side effects
-      a.W = c->lm_head; a.gain = c->final_norm; a.x = h; a.ldx = d; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
-      a.N = cf.vocab; a.K = d;
-      a.amax = (unsigned long long*)(c->ws + c->o.amax);
-      {
-        hipError_t e = gemv_rows<WT, EPI_LOGITS, true>(c, a, rows);
-        if (e != hipSuccess) return e;
-        // clear the selection keys again without touching tokens or state
-        hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state),
-                           (unsigned long long*)(c->ws + c->o.amax), (int*)nullptr, (int*)nullptr, cf.max_seq_len, rows, 0, 0);
-        return hipGetLastError();
-      }
-
-    }
-    default: {
-      // attention for `rows` query rows per sequence ending at the newest cached position
-      const int last = c->sched.n_tok - 1;
-      const int r = rows <= last + 1 ? rows : 1;
-      return launch_attention<WT>(c, l, qkv, attn, (int)POS_EXPLICIT, last - r + 1, r, c->share_kv);
-    }
+      a.W = w.gate; a.W2 = w.up; a.gain = w.mlp_norm; a.x = R.h; a.ldx = d; a.y = mlp; a.ldy = ff; a.N = ff; a.K = d;
+      return gemv_rows<float, EPI_SWIGLU, true>(c, a, rows);
+    default:
+      a.W = w.down; a.x = mlp; a.ldx = ff; a.y = R.h; a.ldy = d; a.N = d; a.K = ff;
+      return gemv_rows<float, EPI_RESID, false>(c, a, rows);
   }
 }
 
@@ -517,7 +662,8 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   c->stream = (hipStream_t)cfg->stream;
   c->sched.n_layers = cfg->n_layers;
   c->sched.max_seq_len = cfg->max_seq_len;
-  c->max_rows = rows_cap(*cfg);
+  c->packed = cfg->dtype == DMTD_DTYPE_BF16;
+  c->ssp_ld = cfg->max_batch * kMaxRows;
   if (!cfg->dry_run) {
     c->wbase = (const char*)weights_dev;
     c->ws = (char*)workspace_dev;
@@ -546,9 +692,29 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
     std::vector<double> inv(hd / 2);
     for (size_t i = 0; i < hd / 2; ++i) inv[i] = std::pow((double)cfg->rope_theta, -2.0 * (double)i / (double)hd);
     hipError_t e = hipMemcpyAsync(c->ws + lay.inv_freq, inv.data(), inv.size() * 8, hipMemcpyHostToDevice, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)cfg->max_batch * 8, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)AMAX_CELLS * cfg->max_batch * 8, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, 256, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
+    if (e == hipSuccess && c->packed) {
+      // one-time repack of every matrix into MFMA operand order (q, k, v are contiguous: one fused matrix)
+      bf16_t* dst = (bf16_t*)(c->ws + lay.wsw);
+      auto swz = [&](const void* src, size_t N, size_t K) {
+        const bf16_t* out = dst;
+        hipLaunchKernelGGL(swizzle_weights_kernel, dim3(2048), dim3(256), 0, c->stream, (const bf16_t*)src, dst, (int)N, (int)K);
+        dst += swizzled_elems(N, K);
+        return out;
+      };
+      const size_t nqkv = qd + 2 * kd;
+      c->sw.resize(cfg->n_layers);
+      for (int l = 0; l < cfg->n_layers; ++l) {
+        const LayerW& w = c->layers[l];
+        LayerSw& s = c->sw[l];
+        s.qkv = swz(w.q, nqkv, d); s.o = swz(w.o, d, qd); s.gate = swz(w.gate, ff, d); s.up = swz(w.up, ff, d);
+        s.down = swz(w.down, d, ff);
+      }
+      c->lm_head_sw = swz(c->lm_head, cfg->vocab, d);
+      e = hipGetLastError();
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { g_create_error = std::string("workspace setup: ") + hipGetErrorString(e); delete c; return DMTD_EHIP; }
   }
@@ -572,12 +738,11 @@ int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prom
     int* dtok = (int*)(c->ws + c->o.tokens);
     HIP_TRY(c, hipMemcpy2DAsync(dtok, (size_t)cf.max_seq_len * 4, tokens, (size_t)prompt_len * 4, (size_t)prompt_len * 4, batch,
                                 hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, cf.dtype == DMTD_DTYPE_F32 ? enqueue_prefill<float>(c, prompt_len, n_late) : enqueue_prefill<bf16_t>(c, prompt_len, n_late));
+    HIP_TRY(c, enqueue_prefill(c, prompt_len, n_late));
     std::vector<int32_t> first(batch);
     HIP_TRY(c, hipMemcpyAsync(first.data(), c->ws + c->o.emitted, (size_t)batch * 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (first_tokens) std::memcpy(first_tokens, first.data(), (size_t)batch * 4);
-    c->have_logits = true;
   } else if (first_tokens) {
     for (int b = 0; b < batch; ++b) first_tokens[b] = -1;
   }
@@ -721,12 +886,10 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
     c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
   }
   if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }
-  if (kind == DMTD_K_ATTN && rows > c->max_rows) { c->err = "too many rows for the attention kernel"; return DMTD_EINVAL; }
   if (kind == DMTD_K_LMHEAD && rows > c->batch) { c->err = "the LM head carries one row per sequence"; return DMTD_EINVAL; }
   hipEvent_t e0, e1;
   HIP_TRY(c, hipEventCreate(&e0));
   HIP_TRY(c, hipEventCreate(&e1));
-  const bool f32 = c->cfg.dtype == DMTD_DTYPE_F32;
   // rows is per sequence for attention, total activation rows for the projections
   const int saved_batch = c->batch;
   long launches = 0;
@@ -736,11 +899,11 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
     if (pass == 1) e = hipEventRecord(e0, c->stream);
     for (int i = 0; i < n && e == hipSuccess; ++i) {
       if (kind == DMTD_K_LMHEAD) {
-        e = f32 ? time_one<float>(c, kind, 0, rows) : time_one<bf16_t>(c, kind, 0, rows);
+        e = time_one(c, kind, 0, rows);
         if (pass == 1) launches += 1;
       } else {
         for (int l = 0; l < c->cfg.n_layers && e == hipSuccess; ++l) {
-          e = f32 ? time_one<float>(c, kind, l, rows) : time_one<bf16_t>(c, kind, l, rows);
+          e = time_one(c, kind, l, rows);
           if (pass == 1) launches += 1;
         }
       }
@@ -768,7 +931,6 @@ int dmtd_reset(dmtd_ctx* c) {
   }
   c->sched.reset();
   c->batch = 0;
-  c->have_logits = false;
   return DMTD_OK;
 }
 

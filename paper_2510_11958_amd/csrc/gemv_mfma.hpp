@@ -1,135 +1,316 @@
-// MFMA weight-streaming "skinny GEMM" for 2..16 activation rows of a bf16 model on gfx950.
+// MFMA weight-streaming "skinny GEMM" for 1..16 activation rows of a bf16 model on gfx950.
 //
 // y[m, n] = sum_k W[n, k] * xhat[m, k].  The weights are the A operand of
-// v_mfma_f32_16x16x32_bf16 and are loaded from HBM straight into the operand registers:
-// lane (row = lane % 16, kg = lane / 16) owns 32 contiguous bytes of its row per k-step of
-// 64 elements, so the four lanes of a row fetch one whole 128-byte line and every weight
-// byte is read exactly once.  The activation rows are the B operand (column = lane % 16),
-// converted to bf16 on the way in; columns beyond M are zero.  The order of k inside a
-// k-step is permuted identically for A and B (first MFMA: elements kg*16 + 0..7, second:
-// kg*16 + 8..15), which a dot product does not notice.  No cross-lane reduction is needed:
-// the matrix core sums over k, and a lane ends up holding 4 rows of one output column.
+// v_mfma_f32_16x16x32_bf16.  They are stored in HBM in operand order ("swizzled", done once
+// at context creation): for each tile of 16 output rows and each k-step of 64 elements,
+// two 1 KiB pieces, piece h holding for lane l = (kg = l / 16, r = l % 16) the 8 elements
+// W[16 t + r][64 s + 32 h + 8 kg + 0..7].  One load instruction of a wave therefore reads
+// 1 KiB of contiguous memory straight into the operand registers, every weight byte is
+// read exactly once, and no data passes through LDS or is converted on the way.
+//
+// The activation rows are the B operand (column = lane % 16, zero beyond M); they arrive
+// already packed in bf16, written by the kernel that produced them.  RMSNorm is folded in
+// exactly: the producer stores bf16(x * gain) and per-tile partial sums of x^2, and the
+// epilogue here multiplies column m by rsqrt(mean(x_m^2) + eps).  No cross-lane reduction
+// is needed: the matrix core sums over k, and a lane ends up holding 4 rows of one column.
 //
 // A block owns one tile of 16 output rows (SwiGLU: the gate tile and the up tile of the
-// same 16 outputs); its waves split K into runs of at most PF k-steps, all loads of a wave
-// are issued at once, and the waves' partial tiles are summed through LDS in wave order.
-// RMSNorm is folded in exactly: the B operand carries x*gain and the epilogue multiplies
-// column m by rsqrt(mean(x_m^2) + eps), whose sum of squares the waves gather on the way.
+// same 16 outputs); its waves split K into runs of k-steps, a wave issues all loads of a
+// run (up to PF k-steps = 2*PF KiB) at once, and the waves' partial tiles are summed
+// through LDS in wave order (deterministic).  Epilogues: fp32 store (QKV), SwiGLU to packed
+// bf16, residual add that also emits the next norm's packed input and partial sums of
+// squares, and logits with greedy-selection keys.
 #pragma once
 #include "gemv.hpp"
 
 namespace dmtd {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
+// two floats to one packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t to_bf16_hw(float v) { return (bf16_t)(pack_bf16x2(v, 0.f) & 0xFFFFu); }
 
 constexpr int MFMA_MAX_WAVES = 16;   // waves that split K for one tile
+constexpr int AMAX_CELLS = 64;       // selection keys are spread over this many cells per sequence
 
-template <int EPI, bool NORM, int PF>
-__global__ void __launch_bounds__(1024) gemv_mfma_kernel(GemvArgs a, int M, int nw) {
+// Elements of the swizzled image of an [N, K] matrix (rows padded to a multiple of 16).
+__host__ __device__ inline size_t swizzled_elems(size_t N, size_t K) { return (N + 15) / 16 * 16 * K; }
+
+// One-time repack of a row-major [N, K] bf16 matrix (K a multiple of 64) into operand order.
+__global__ void swizzle_weights_kernel(const bf16_t* __restrict__ W, bf16_t* __restrict__ out, int N, int K) {
+  const int KS = K >> 6;
+  const size_t n_chunks = (size_t)((N + 15) / 16) * KS * 2 * 64;     // 16-byte chunks
+  for (size_t ch = blockIdx.x * (size_t)blockDim.x + threadIdx.x; ch < n_chunks; ch += (size_t)gridDim.x * blockDim.x) {
+    const int l = ch & 63, h = (ch >> 6) & 1;
+    const size_t ts = ch >> 7;
+    const int s = ts % KS;
+    const size_t t = ts / KS;
+    const size_t n = t * 16 + (l & 15);
+    u32x4 v = {0, 0, 0, 0};
+    if (n < (size_t)N) v = *(const u32x4*)(W + n * K + (size_t)s * 64 + h * 32 + (l >> 4) * 8);
+    *(u32x4*)(out + ch * 8) = v;
+  }
+}
+
+struct MfmaArgs {
+  const bf16_t* W;       // swizzled [N, K]; SwiGLU: the gate matrix
+  const bf16_t* W2;      // SwiGLU: the up matrix
+  const bf16_t* xb;      // packed activations [M, ldxb] (already multiplied by the norm gain if NORM)
+  int ldxb, M, N, K;
+  const float* ssp;      // NORM: partial sums of squares [n_parts, ssp_ld]
+  int n_parts, ssp_ld;
+  float eps;
+  float* y;              // STORE / LOGITS: fp32 out [M, ldy]; RESID: the residual stream, updated in place
+  int ldy;
+  bf16_t* yb;            // SwiGLU: packed out [M, ldyb]; RESID: packed input of the next norm (h * g_next)
+  int ldyb;
+  const bf16_t* g_next;  // RESID: gain of the next norm [N]
+  float* ssp_next;       // RESID: partial sums of squares of the updated residual rows [tiles, ssp_ld]
+  unsigned long long* amax;   // LOGITS: selection keys [AMAX_CELLS, amax_ld], already offset to this launch's rows
+  int amax_ld;
+};
+
+// BLDS: the block first copies the M packed activation rows into LDS (dynamic shared memory,
+// M * (K + 8) * 2 bytes) and the waves take their B operands from there, which frees the
+// registers a wave would need to hold them; without it each wave loads its B operands from
+// global memory into registers (for M * K too large for LDS).
+template <int EPI, bool NORM, int PF, int NWT, bool BLDS>   // NWT: waves per block (all matrices)
+__global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
+  extern __shared__ float4 dyn_smem[];
+  bf16_t* xs = (bf16_t*)dyn_smem;                        // BLDS: [M][K + 8]
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
-  __shared__ float red[MATS][MFMA_MAX_WAVES][16][16];   // [matrix][wave][row][column]
-  __shared__ float ssred[MFMA_MAX_WAVES][16];
+  constexpr int nw = NWT / MATS;                         // waves that split K for one matrix
+  static_assert(nw >= 1 && nw <= MFMA_MAX_WAVES, "waves per tile");
+  __shared__ float red[MATS][nw][16][17];               // [matrix][wave][column][row], padded
+  __shared__ float ss_s[16][17];
+  constexpr int SS_ITEMS = 16 * 256;                    // partial sums staged in LDS (hidden sizes up to 4096)
+  __shared__ float ss_items[NORM ? SS_ITEMS : 1];
+  __shared__ float rs_s[16];
+  __shared__ unsigned long long key_s[16];
   const int tid = threadIdx.x, lane = tid & 63, wall = tid >> 6;
   const int mat = wall / nw, w = wall % nw;
-  const int r = lane & 15, kg = lane >> 4;     // A: row r of the tile; B and D: column r
-  const int K = a.K, N = a.N;
+  const int r = lane & 15, kg = lane >> 4;     // B and D: column r
+  const int K = a.K, N = a.N, M = a.M;
   const int tile = blockIdx.x;
   const int KS = K >> 6;                       // k-steps of 64 elements
   const int s0 = (int)((long)w * KS / nw), s1 = (int)((long)(w + 1) * KS / nw);
 
-  const bf16_t* __restrict__ Wm = (const bf16_t*)(mat == 0 ? a.W : a.W2);
-  const bf16_t* arow = Wm + (size_t)min(tile * 16 + r, N - 1) * K + kg * 16;
-  u32x4 A[PF][2];
-#pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    const int s = s0 + i;
-    if (s < s1) {
-      A[i][0] = __builtin_nontemporal_load((const u32x4*)(arow + (size_t)s * 64));
-      A[i][1] = __builtin_nontemporal_load((const u32x4*)(arow + (size_t)s * 64 + 8));
-    } else {
-      A[i][0] = u32x4{0, 0, 0, 0}; A[i][1] = A[i][0];
-    }
-  }
-
-  // B operand: column r (activation row r) of this wave's k-range, times the norm gain
+  const bf16_t* __restrict__ abase = (mat == 0 ? a.W : a.W2) + ((size_t)tile * KS) * 1024 + lane * 8;
   const bool colact = r < M;
-  const float* xrow = a.x + (size_t)(colact ? r : 0) * a.ldx + kg * 16;
-  const bf16_t* grow = (const bf16_t*)a.gain + kg * 16;
-  u32x4 B[PF][2];
-  float ss = 0.f;
+  const bf16_t* __restrict__ bbase = a.xb + (size_t)(colact ? r : 0) * a.ldxb + kg * 8;
+  const int ldxs = K + 8;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+
+  // small loads first (they return first): the B rows for LDS and the partial sums of squares
+  constexpr int NT = 64 * NWT;
+  u32x4 bst[4];
+  const int k8 = K >> 3, n_chunks = M * k8;
+  if (BLDS) {
 #pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    const int s = s0 + i;
-    B[i][0] = u32x4{0, 0, 0, 0}; B[i][1] = B[i][0];
-    if (s < s1 && colact) {
-      float xv[16];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 v = *(const float4*)(xrow + (size_t)s * 64 + q * 4);
-        xv[q * 4 + 0] = v.x; xv[q * 4 + 1] = v.y; xv[q * 4 + 2] = v.z; xv[q * 4 + 3] = v.w;
-      }
-      if (NORM) {
-        float gv[16];
-        float g8[8];
-        Elem<bf16_t>::unpack(*(const u32x4*)(grow + (size_t)s * 64), g8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) gv[e] = g8[e];
-        Elem<bf16_t>::unpack(*(const u32x4*)(grow + (size_t)s * 64 + 8), g8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) gv[8 + e] = g8[e];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { ss += xv[e] * xv[e]; xv[e] *= gv[e]; }
-      }
-      B[i][0] = u32x4{pack_bf16x2(xv[0], xv[1]), pack_bf16x2(xv[2], xv[3]), pack_bf16x2(xv[4], xv[5]), pack_bf16x2(xv[6], xv[7])};
-      B[i][1] = u32x4{pack_bf16x2(xv[8], xv[9]), pack_bf16x2(xv[10], xv[11]), pack_bf16x2(xv[12], xv[13]), pack_bf16x2(xv[14], xv[15])};
+    for (int j = 0; j < 4; ++j) {
+      const int idx = tid + j * NT;
+      if (idx < n_chunks) bst[j] = *(const u32x4*)(a.xb + (size_t)(idx / k8) * a.ldxb + (idx % k8) * 8);
     }
   }
-
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  u32x4 A[PF][2];
+  auto load_a = [&](int base) {
 #pragma unroll
-  for (int i = 0; i < PF; ++i) {
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, B[i][0]), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, B[i][1]), acc, 0, 0, 0);
+    for (int i = 0; i < PF; ++i) {
+      const int s = base + i;
+      if (s < s1) {
+        A[i][0] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024));
+        A[i][1] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024 + 512));
+      } else {
+        A[i][0] = u32x4{0, 0, 0, 0}; A[i][1] = A[i][0];
+      }
+    }
+  };
+  load_a(s0);                                             // the weight stream starts before anything waits
+  if (NORM) {
+    // the producer's partial sums of squares, M * n_parts floats, fetched by all threads while the weights fly
+    const int n_items = M * a.n_parts;
+    for (int i = tid; i < n_items && i < SS_ITEMS; i += NT) ss_items[i] = a.ssp[(size_t)(i / M) * a.ssp_ld + (i % M)];
+  }
+  if (BLDS) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int idx = tid + j * NT;
+      if (idx < n_chunks) *(u32x4*)(xs + (size_t)(idx / k8) * ldxs + (idx % k8) * 8) = bst[j];
+    }
+    for (int idx = tid + 4 * NT; idx < n_chunks; idx += NT)      // rows beyond what the early loads covered
+      *(u32x4*)(xs + (size_t)(idx / k8) * ldxs + (idx % k8) * 8) = *(const u32x4*)(a.xb + (size_t)(idx / k8) * a.ldxb + (idx % k8) * 8);
+    __syncthreads();
+  }
+
+  for (int base = s0; base < s1; base += PF) {           // one round unless the wave's k-range exceeds PF steps
+    if (base != s0) load_a(base);
+    if (BLDS) {
+      const bf16_t* xrow = xs + (size_t)(colact ? r : 0) * ldxs + kg * 8;
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        const int s = base + i;
+        u32x4 b0 = {0, 0, 0, 0}, b1 = b0;
+        if (s < s1 && colact) {
+          b0 = *(const u32x4*)(xrow + (size_t)s * 64);
+          b1 = *(const u32x4*)(xrow + (size_t)s * 64 + 32);
+        }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
+      }
+    } else {
+      u32x4 B[PF][2];
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        const int s = base + i;
+        B[i][0] = u32x4{0, 0, 0, 0}; B[i][1] = B[i][0];
+        if (s < s1 && colact) {
+          B[i][0] = *(const u32x4*)(bbase + (size_t)s * 64);
+          B[i][1] = *(const u32x4*)(bbase + (size_t)s * 64 + 32);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, B[i][0]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, B[i][1]), acc, 0, 0, 0);
+      }
+    }
   }
   // lane (column r, kg) holds rows kg*4 .. kg*4+3 of column r
   if (colact) {
-    red[mat][w][kg * 4 + 0][r] = acc.x; red[mat][w][kg * 4 + 1][r] = acc.y;
-    red[mat][w][kg * 4 + 2][r] = acc.z; red[mat][w][kg * 4 + 3][r] = acc.w;
+    red[mat][w][r][kg * 4 + 0] = acc.x; red[mat][w][r][kg * 4 + 1] = acc.y;
+    red[mat][w][r][kg * 4 + 2] = acc.z; red[mat][w][r][kg * 4 + 3] = acc.w;
   }
-  if (NORM && mat == 0) {
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (kg == 0) ssred[w][r] = ss;
-  }
+  if (EPI == EPI_LOGITS && tid < 16) key_s[tid] = 0ull;
   __syncthreads();
-  for (int t = tid; t < 256; t += blockDim.x) {
-    const int row = t >> 4, c = t & 15, n = tile * 16 + row;
-    if (c >= M || n >= N) continue;
-    float rs = 1.f;
-    if (NORM) {
+  if (NORM) {
+    // per column: 16 threads sum interleaved parts, then one thread sums the 16 (fixed order: deterministic)
+    for (int t = tid; t < 256; t += NT) {
+      const int c = t >> 4, j = t & 15;
       float s = 0.f;
-      for (int ww = 0; ww < nw; ++ww) s += ssred[ww][c];
-      rs = rsqrtf(s / (float)K + a.eps);
+      if (c < M) {
+        for (int p = j; p < a.n_parts; p += 16) {
+          const int i = p * M + c;
+          s += i < SS_ITEMS ? ss_items[i] : a.ssp[(size_t)p * a.ssp_ld + c];
+        }
+      }
+      ss_s[c][j] = s;
     }
-    float v0 = 0.f;
-    for (int ww = 0; ww < nw; ++ww) v0 += red[0][ww][row][c];
-    v0 *= rs;
-    float* dst = a.y + (size_t)c * a.ldy + n;
-    if (EPI == EPI_SWIGLU) {
-      float v1 = 0.f;
-      for (int ww = 0; ww < nw; ++ww) v1 += red[MATS - 1][ww][row][c];
-      v1 *= rs;
-      *dst = v0 / (1.0f + __expf(-v0)) * v1;
-    } else if (EPI == EPI_RESID) {
-      *dst += v0;
-    } else {
-      *dst = v0;
+    __syncthreads();
+    if (tid < 16) {
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += ss_s[tid][j];
+      rs_s[tid] = rsqrtf(s / (float)K + a.eps);
+    }
+    __syncthreads();
+  }
+
+  for (int t = tid; t < 256; t += 64 * NWT) {
+    const int c = t >> 4, row = t & 15, n = tile * 16 + row;
+    float hsq = 0.f;
+    if (c < M && n < N) {
+      const float rs = NORM ? rs_s[c] : 1.f;
+      float v0 = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < nw; ++ww) v0 += red[0][ww][c][row];
+      v0 *= rs;
+      if (EPI == EPI_SWIGLU) {
+        float v1 = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < nw; ++ww) v1 += red[MATS - 1][ww][c][row];
+        v1 *= rs;
+        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(v0 / (1.0f + __expf(-v0)) * v1);
+      } else if (EPI == EPI_RESID) {
+        float* dst = a.y + (size_t)c * a.ldy + n;
+        const float hn = *dst + v0;
+        *dst = hn;
+        hsq = hn * hn;
+        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(hn * bf16_to_f32(a.g_next[n]));
+      } else {
+        a.y[(size_t)c * a.ldy + n] = v0;
+        if (EPI == EPI_LOGITS) atomicMax(&key_s[c], argmax_key(v0, n));
+      }
+    }
+    if (EPI == EPI_RESID) ss_s[c][row] = hsq;
+  }
+  if (EPI == EPI_RESID) {
+    __syncthreads();
+    if (tid < M) {
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += ss_s[tid][j];
+      a.ssp_next[(size_t)tile * a.ssp_ld + tid] = s;
     }
   }
+  if (EPI == EPI_LOGITS) {
+    __syncthreads();
+    if (tid < M && key_s[tid] != 0ull) atomicMax(a.amax + (size_t)(tile % AMAX_CELLS) * a.amax_ld + tid, key_s[tid]);
+  }
+}
+
+// Row-wise helper for the packed path: from an fp32 row h write the packed input of a norm,
+// bf16(h * gain), and the row's sum of squares as a single partial (n_parts = 1).
+// Call with all threads of the block; contains a barrier.
+__device__ __forceinline__ void pack_row_for_norm(const float* __restrict__ h, const bf16_t* __restrict__ gain, int d,
+                                                  bf16_t* __restrict__ xb, float* __restrict__ ssp_slot) {
+  __shared__ float wsum[16];
+  float ss = 0.f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    const float v = h[k];
+    ss += v * v;
+    xb[k] = to_bf16_hw(v * bf16_to_f32(gain[k]));
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += wsum[w];
+    *ssp_slot = s;
+  }
+}
+
+// ---- row kernels of the packed (bf16) path: like their fp32 counterparts, and they also
+// ---- emit the packed input and the sum of squares for the norm that reads the rows next
+
+__global__ void __launch_bounds__(256) embed_pack_kernel(
+    const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset,
+    int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+  const int row = blockIdx.x, b = row / r, i = row % r;
+  const int pos = row_base(st, sel, offset) + i;
+  const bf16_t* src = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
+  float* dst = h + (size_t)row * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = bf16_to_f32(src[k]);
+  pack_row_for_norm(dst, gain, d, xb + (size_t)row * d, ssp + row);
+}
+
+__global__ void __launch_bounds__(256) take_last_pack_kernel(
+    const float* __restrict__ src, float* __restrict__ dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
+    const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset, const bf16_t* __restrict__ gain,
+    bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+  const int b = blockIdx.x;
+  const float* s = src + ((size_t)b * r + (r - 1)) * d;
+  float* o = dst + (size_t)b * d;
+  const bf16_t* e = nullptr;
+  if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + r - 1] * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? bf16_to_f32(e[k]) : 0.0f);
+  pack_row_for_norm(o, gain, d, xb + (size_t)b * d, ssp + b);
+}
+
+__global__ void __launch_bounds__(256) add_embed_pack_kernel(
+    float* __restrict__ h, const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st,
+    int sel, int offset, int r, int d, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+  const int row = blockIdx.x, b = row / r, i = row % r;
+  const bf16_t* e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + i] * d;
+  float* o = h + (size_t)row * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += bf16_to_f32(e[k]);
+  pack_row_for_norm(o, gain, d, xb + (size_t)row * d, ssp + row);
 }
 
 }  // namespace dmtd

@@ -122,16 +122,21 @@ __device__ __forceinline__ unsigned long long argmax_key(float v, int idx) {
 }
 __device__ __forceinline__ int argmax_key_index(unsigned long long key) { return 0x7FFFFFFF - (int)(uint32_t)(key & 0xFFFFFFFFu); }
 
-// End of a step: turn each sequence's selection key into its token (written to the step's
+// End of a step: turn each sequence's selection keys into its token (written to the step's
 // output slot and, unless the caller forces the next input, to the token history), clear the
 // keys, and advance the state: one more token is in the late caches; a full step also closes
 // the refill gap.  With write_tokens == 0 only the keys are cleared (measurement launches).
-__global__ void finish_step_kernel(DevState* st, unsigned long long* amax, int* tokens, int* emitted, int s_max, int batch,
-                                   int full, int write_tokens) {
+__global__ void finish_step_kernel(DevState* st, unsigned long long* amax, int n_cells, int amax_ld, int* tokens, int* emitted,
+                                   int s_max, int batch, int full, int write_tokens) {
   const int pos = st->n_tok, step = st->step_idx, forced_until = st->forced_until;
   for (int b = threadIdx.x; b < batch; b += blockDim.x) {
-    const int tok = argmax_key_index(amax[b]);
-    amax[b] = 0ull;
+    unsigned long long best = 0ull;      // keys are spread over n_cells cells per sequence
+    for (int c = 0; c < n_cells; ++c) {
+      const unsigned long long k = amax[(size_t)c * amax_ld + b];
+      if (k > best) best = k;
+      amax[(size_t)c * amax_ld + b] = 0ull;
+    }
+    const int tok = argmax_key_index(best);
     if (write_tokens) {
       emitted[step * batch + b] = tok;
       if (pos + 1 < s_max && pos + 1 >= forced_until) tokens[(size_t)b * s_max + pos + 1] = tok;
