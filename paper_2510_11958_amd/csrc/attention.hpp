@@ -39,6 +39,83 @@ __device__ __forceinline__ int att_keys_per_split(int ctx, int n_splits, int kpi
   return ((ctx + n_splits - 1) / n_splits + kpi - 1) / kpi * kpi;
 }
 
+// One block iteration of the running softmax: 4 keys per lane group (kf, vf: this lane's 8 dims of
+// each), scored against every query vector.  After the in-group reduction lane slice sl holds the
+// score of key u = sl >> USH, whose position is my_key; keys at or beyond key_end, or beyond the
+// row's own position (row i = qv / GQ sees keys <= pos0 + i), are masked.
+template <int HD, int QVT>
+__device__ __forceinline__ void attn_accumulate(const float (&q)[QVT][8], const float (&kf)[4][8], const float (&vf)[4][8],
+                                                int my_key, int key_end, int pos0, int GQ, int QV, int lane, int sl,
+                                                float (&m)[QVT], float (&l)[QVT], float (&acc)[QVT][8]) {
+  constexpr int LPK = HD / 8, U = 4;
+  constexpr int USH = LPK == 16 ? 2 : 1;
+#pragma unroll
+for (int qv = 0; qv < QVT; ++qv) {
+  if (qv < QV) {
+    float s4[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d += q[qv][e] * kf[u][e];
+      s4[u] = d;
+    }
+    // sum over the lane group; the 4 keys' sums end up in 4 different lane slices
+    {
+      const bool up1 = (sl & (LPK / 2)) != 0;
+      const float a0 = (up1 ? s4[2] : s4[0]) + __shfl_xor(up1 ? s4[0] : s4[2], LPK / 2, 64);
+      const float a1 = (up1 ? s4[3] : s4[1]) + __shfl_xor(up1 ? s4[1] : s4[3], LPK / 2, 64);
+      const bool up2 = (sl & (LPK / 4)) != 0;
+      float s = (up2 ? a1 : a0) + __shfl_xor(up2 ? a0 : a1, LPK / 4, 64);
+#pragma unroll
+      for (int o = LPK / 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      s4[0] = s;
+    }
+    // causal and range mask: row i = qv / GQ sees keys <= pos0 + i
+    float s = s4[0];
+    if (my_key >= key_end || my_key > pos0 + qv / GQ) s = -INFINITY;
+    float mx = s;
+#pragma unroll
+    for (int o = LPK / 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));   // over keys and lane groups
+    const float m_new = fmaxf(m[qv], mx);
+    if (m_new != -INFINITY) {
+      const float sc = __expf(m[qv] - m_new);           // exp(-inf) = 0 on the first visible key
+      const float p = (s == -INFINITY) ? 0.f : __expf(s - m_new);
+      l[qv] = l[qv] * sc + p;
+      float pu[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) pu[u] = __shfl(p, (lane & ~(LPK - 1)) | (u << USH), 64);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        acc[qv][e] = acc[qv][e] * sc + ((pu[0] * vf[0][e] + pu[1] * vf[1][e]) + (pu[2] * vf[2][e] + pu[3] * vf[3][e]));
+      m[qv] = m_new;
+    }
+  }
+}
+}
+
+// End of a wave's key loop: l summed over the distinct (lane group, key) holders, acc over the lane groups.
+template <int HD, int QVT>
+__device__ __forceinline__ void attn_wave_totals(float (&l)[QVT], float (&acc)[QVT][8]) {
+  constexpr int LPK = HD / 8;
+#pragma unroll
+  for (int qv = 0; qv < QVT; ++qv) {
+    float v = l[qv];
+#pragma unroll
+    for (int o = LPK / 4; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+    l[qv] = v;
+  }
+#pragma unroll
+  for (int qv = 0; qv < QVT; ++qv)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[qv][e];
+#pragma unroll
+      for (int o = LPK; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+      acc[qv][e] = v;
+    }
+}
+
 template <typename CT, int HD, int QVT>
 __global__ void __launch_bounds__(256) attn_decode_kernel(
     const float* __restrict__ qkv, int ldq, const CT* __restrict__ kc, const CT* __restrict__ vc,
@@ -116,68 +193,10 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
         for (int u = 0; u < U; ++u) { Elem<CT>::unpack(kr[u], kf[u]); Elem<CT>::unpack(vr[u], vf[u]); }
       }
       const int my_key = it0 + my_u * NG + grp;       // the key whose score this lane will hold
-#pragma unroll
-      for (int qv = 0; qv < QVT; ++qv) {
-        if (qv < QV) {
-          float s4[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            float d = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) d += q[qv][e] * kf[u][e];
-            s4[u] = d;
-          }
-          // sum over the lane group; the 4 keys' sums end up in 4 different lane slices
-          {
-            const bool up1 = (sl & (LPK / 2)) != 0;
-            const float a0 = (up1 ? s4[2] : s4[0]) + __shfl_xor(up1 ? s4[0] : s4[2], LPK / 2, 64);
-            const float a1 = (up1 ? s4[3] : s4[1]) + __shfl_xor(up1 ? s4[1] : s4[3], LPK / 2, 64);
-            const bool up2 = (sl & (LPK / 4)) != 0;
-            float s = (up2 ? a1 : a0) + __shfl_xor(up2 ? a0 : a1, LPK / 4, 64);
-#pragma unroll
-            for (int o = LPK / 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-            s4[0] = s;
-          }
-          // causal and range mask: row i = qv / GQ sees keys <= pos0 + i
-          float s = s4[0];
-          if (my_key >= key_end || my_key > pos0 + qv / GQ) s = -INFINITY;
-          float mx = s;
-#pragma unroll
-          for (int o = LPK / 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));   // over keys and lane groups
-          const float m_new = fmaxf(m[qv], mx);
-          if (m_new != -INFINITY) {
-            const float sc = __expf(m[qv] - m_new);           // exp(-inf) = 0 on the first visible key
-            const float p = (s == -INFINITY) ? 0.f : __expf(s - m_new);
-            l[qv] = l[qv] * sc + p;
-            float pu[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) pu[u] = __shfl(p, (lane & ~(LPK - 1)) | (u << USH), 64);
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              acc[qv][e] = acc[qv][e] * sc + ((pu[0] * vf[0][e] + pu[1] * vf[1][e]) + (pu[2] * vf[2][e] + pu[3] * vf[3][e]));
-            m[qv] = m_new;
-          }
-        }
-      }
+      attn_accumulate<HD, QVT>(q, kf, vf, my_key, key_end, pos0, GQ, QV, lane, sl, m, l, acc);
     }
 
-    // wave totals: l over the distinct (lane group, key) holders, acc over the lane groups
-#pragma unroll
-    for (int qv = 0; qv < QVT; ++qv) {
-      float v = l[qv];
-#pragma unroll
-      for (int o = LPK / 4; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
-      l[qv] = v;
-    }
-#pragma unroll
-    for (int qv = 0; qv < QVT; ++qv)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = acc[qv][e];
-#pragma unroll
-        for (int o = LPK; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
-        acc[qv][e] = v;
-      }
+    attn_wave_totals<HD, QVT>(l, acc);
     if (lane < LPK) {
 #pragma unroll
       for (int qv = 0; qv < QVT; ++qv)
@@ -248,6 +267,159 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(
       o += (f == 0.f) ? 0.f : f * v;      // splits without visible keys hold stale partials: weight 0, value ignored
     }
     out[(size_t)(b * r_total + i) * ldo + (size_t)(g * GQ + j) * HD + d] = Elem<OT>::from_f32(o * inv_l[j]);
+  }
+}
+
+// Short-context variant: ONE kernel per layer does QK-RMSNorm + RoPE of the new rows, the KV-cache
+// append, the whole attention over the sequence and the normalisation.  A block is (row group,
+// KV head, sequence) and walks all keys itself with NW waves, so there is no split to merge and
+// nothing another block must see: the new keys and values are formed in LDS from the raw
+// projections (rounded to the cache's type, exactly what later steps will read back) and the
+// last row group's block also writes them to the cache.  Used while the K/V of a sequence is
+// small enough that a handful of blocks can pull it without starving the chip.
+template <typename CT, typename OT, int HD, int QVT, int NW>
+__global__ void __launch_bounds__(64 * NW) attn_fused_kernel(
+    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
+    const double* __restrict__ inv_freq, CT* __restrict__ kc, CT* __restrict__ vc, OT* __restrict__ out, int ldo,
+    int nh, int nkv, int s_max, float eps, const DevState* st, int sel, int offset, int r_total) {
+  typedef typename Elem<CT>::Raw Raw;
+  constexpr int LPK = HD / 8, GPW = 64 / LPK, NG = NW * GPW, U = 4, KPI = NG * U;
+  constexpr int USH = LPK == 16 ? 2 : 1;
+  constexpr int NEW_MAX = 16;                                   // rows a launch can carry
+  const int rg = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int GQ = nh / nkv, rpb = QVT / GQ;
+  const int r = min(rpb, r_total - rg * rpb), QV = r * GQ;
+  const int pos_first = row_base(st, sel, offset);
+  const int pos0 = pos_first + rg * rpb, ctx = pos0 + r;
+  const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
+  const bool writer = (rg + 1) * rpb >= r_total;                // the last row group's block appends to the cache
+  const float scale = rsqrtf((float)HD);
+
+  __shared__ float q_s[QVT][HD];
+  __shared__ float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
+  __shared__ float wacc[NW][QVT][HD];
+  __shared__ float wm[NW][QVT], wl[NW][QVT];
+
+  // ---- prologue: per-head RMSNorm + RoPE (pair (i, i + HD/2)) of this block's queries and of the new keys
+  {
+    constexpr int half = HD / 2;
+    const bool act = lane < half;
+    const int n_vec = QV + 2 * n_new;                           // queries, new keys, new values
+    for (int v = wave; v < n_vec; v += NW) {
+      if (v < QV + n_new) {
+        const bool is_q = v < QV;
+        const int row = is_q ? rg * rpb + v / GQ : v - QV;      // row of the launch
+        const int head = is_q ? g * GQ + v % GQ : nh + g;
+        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)head * HD;
+        float x0 = act ? src[lane] : 0.f, x1 = act ? src[lane + half] : 0.f;
+        const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)HD + eps);
+        if (act) {
+          const CT* gn = (const CT*)(is_q ? q_gain : k_gain);
+          x0 *= rs * Elem<CT>::to_f32(gn[lane]);
+          x1 *= rs * Elem<CT>::to_f32(gn[lane + half]);
+          double sn, cs;
+          sincos((double)(pos_first + row) * inv_freq[lane], &sn, &cs);
+          const float c = (float)cs, sf = (float)sn;
+          const float y0 = x0 * c - x1 * sf, y1 = x1 * c + x0 * sf;
+          if (is_q) {
+            q_s[v][lane] = y0 * scale; q_s[v][lane + half] = y1 * scale;
+          } else {
+            const CT c0 = Elem<CT>::from_f32(y0), c1 = Elem<CT>::from_f32(y1);
+            knew_s[row][lane] = Elem<CT>::to_f32(c0); knew_s[row][lane + half] = Elem<CT>::to_f32(c1);
+            if (writer) {
+              CT* dst = kc + (((size_t)b * nkv + g) * s_max + pos_first + row) * HD;
+              dst[lane] = c0; dst[lane + half] = c1;
+            }
+          }
+        }
+      } else {
+        const int row = v - QV - n_new;
+        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)(nh + nkv + g) * HD;
+        CT* dst = vc + (((size_t)b * nkv + g) * s_max + pos_first + row) * HD;
+        for (int k = lane; k < HD; k += 64) {
+          const CT cv = Elem<CT>::from_f32(src[k]);
+          vnew_s[row][k] = Elem<CT>::to_f32(cv);
+          if (writer) dst[k] = cv;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  const int sl = lane % LPK, grp = wave * GPW + lane / LPK;
+  const int my_u = sl >> USH;
+  float q[QVT][8];
+#pragma unroll
+  for (int qv = 0; qv < QVT; ++qv)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[qv][e] = qv < QV ? q_s[qv][sl * 8 + e] : 0.f;
+  float m[QVT], l[QVT], acc[QVT][8];
+#pragma unroll
+  for (int qv = 0; qv < QVT; ++qv) {
+    m[qv] = -INFINITY; l[qv] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[qv][e] = 0.f;
+  }
+  const CT* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
+  const CT* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
+
+  // ---- cached keys 0 .. pos_first-1 (all visible to every row of the block)
+  for (int it0 = 0; it0 < pos_first; it0 += KPI) {
+    float kf[U][8], vf[U][8];
+    {
+      Raw kr[U], vr[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int key = it0 + u * NG + grp;
+        const bool ok = key < pos_first;
+        kr[u] = ok ? Elem<CT>::load_raw(kbase + (size_t)key * HD) : Elem<CT>::zero_raw();
+        vr[u] = ok ? Elem<CT>::load_raw(vbase + (size_t)key * HD) : Elem<CT>::zero_raw();
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) { Elem<CT>::unpack(kr[u], kf[u]); Elem<CT>::unpack(vr[u], vf[u]); }
+    }
+    attn_accumulate<HD, QVT>(q, kf, vf, it0 + my_u * NG + grp, pos_first, pos0, GQ, QV, lane, sl, m, l, acc);
+  }
+  // ---- the new keys pos_first .. ctx-1, from LDS (one iteration: n_new <= 16 <= KPI)
+  {
+    float kf[U][8], vf[U][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = u * NG + grp;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        kf[u][e] = i < n_new ? knew_s[i][sl * 8 + e] : 0.f;
+        vf[u][e] = i < n_new ? vnew_s[i][sl * 8 + e] : 0.f;
+      }
+    }
+    attn_accumulate<HD, QVT>(q, kf, vf, pos_first + my_u * NG + grp, ctx, pos0, GQ, QV, lane, sl, m, l, acc);
+  }
+
+  attn_wave_totals<HD, QVT>(l, acc);
+  if (lane < LPK) {
+#pragma unroll
+    for (int qv = 0; qv < QVT; ++qv)
+      if (qv < QV) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wacc[wave][qv][sl * 8 + e] = acc[qv][e];
+        if (lane == 0) { wm[wave][qv] = m[qv]; wl[wave][qv] = l[qv]; }
+      }
+  }
+  __syncthreads();
+  for (int e = tid; e < QV * HD; e += 64 * NW) {
+    const int qv = e / HD, d = e % HD;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mm = fmaxf(mm, wm[w][qv]);
+    float o = 0.f, ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
+      o += f * wacc[w][qv][d];
+      ll += f * wl[w][qv];
+    }
+    out[(size_t)(b * r_total + rg * rpb + qv / GQ) * ldo + (size_t)(g * GQ + qv % GQ) * HD + d] = Elem<OT>::from_f32(o / ll);
   }
 }
 

@@ -81,6 +81,7 @@ struct dmtd_ctx {
   std::vector<LayerSw> sw;
   std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
+  bool att_fused = false;     // attention launches: the fused short-context kernel
 };
 
 namespace {
@@ -317,6 +318,38 @@ hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, int 
   return hipGetLastError();
 }
 
+// Short contexts: one kernel does QK-norm, RoPE, the cache append and the whole attention (no split, no merge).
+template <typename CT, typename OT, int HD, int QVT, int NW>
+void launch_attention_fused_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
+  const dmtd_config& cf = c->cfg;
+  const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
+  const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
+  const LayerW& w = c->layers[l];
+  CT* kc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  CT* vc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  hipLaunchKernelGGL((attn_fused_kernel<CT, OT, HD, QVT, NW>), dim3(n_rg, cf.n_kv_heads, c->batch), dim3(64 * NW), 0, c->stream,
+                     qkv, nqkv, w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, attn, qd, cf.n_q_heads,
+                     cf.n_kv_heads, cf.max_seq_len, cf.rms_eps, dev_state(c), sel, offset, r);
+}
+
+template <typename CT, typename OT>
+hipError_t launch_attention_fused(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
+  const dmtd_config& cf = c->cfg;
+  const int gq = cf.n_q_heads / cf.n_kv_heads;
+  if (r > kMaxRows) return hipErrorInvalidValue;
+  const int qvt = gq <= 4 ? 4 : (gq <= 8 ? 8 : 16);      // one row (or a few, for small groups) per block
+  if (cf.head_dim == 128) {
+    if (qvt == 4) launch_attention_fused_t<CT, OT, 128, 4, 8>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_fused_t<CT, OT, 128, 8, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_fused_t<CT, OT, 128, 16, 4>(c, l, qkv, attn, sel, offset, r);
+  } else {
+    if (qvt == 4) launch_attention_fused_t<CT, OT, 64, 4, 8>(c, l, qkv, attn, sel, offset, r);
+    else if (qvt == 8) launch_attention_fused_t<CT, OT, 64, 8, 8>(c, l, qkv, attn, sel, offset, r);
+    else launch_attention_fused_t<CT, OT, 64, 16, 4>(c, l, qkv, attn, sel, offset, r);
+  }
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- the steps of a pass
 
 // a1: rows <- embeddings of the tokens at the rows' positions (next reader: the norm of layer next_layer)
@@ -388,12 +421,17 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
     a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
     if ((e = launch_mfma<EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
-    // a3: QK-RMSNorm + RoPE + KV append
-    hipLaunchKernelGGL(qk_norm_rope_append_kernel<bf16_t>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
-                       inv_freq, (bf16_t*)kc, (bf16_t*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
-                       dev_state(c), sel, offset, r);
-    // a4: split-K GQA attention + merge (output packed for the O projection)
-    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
+    if (c->att_fused) {
+      // a3 + a4 in one kernel (short contexts): QK-RMSNorm + RoPE + KV append + attention, packed output
+      if ((e = launch_attention_fused<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
+    } else {
+      // a3: QK-RMSNorm + RoPE + KV append
+      hipLaunchKernelGGL(qk_norm_rope_append_kernel<bf16_t>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
+                         inv_freq, (bf16_t*)kc, (bf16_t*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
+                         dev_state(c), sel, offset, r);
+      // a4: split-K GQA attention + merge (output packed for the O projection)
+      if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
+    }
     // a5: O projection + residual; emits the MLP norm's input
     a = MfmaArgs{};
     a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
@@ -420,12 +458,16 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   // a2: RMSNorm + fused QKV projection (q, k, v are contiguous in the blob)
   a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
   if ((e = gemv_rows<float, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
-  // a3: QK-RMSNorm + RoPE + KV append
-  hipLaunchKernelGGL(qk_norm_rope_append_kernel<float>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
-                     inv_freq, (float*)kc, (float*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
-                     dev_state(c), sel, offset, r);
-  // a4: split-K GQA attention + merge
-  if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
+  if (c->att_fused) {
+    if ((e = launch_attention_fused<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
+  } else {
+    // a3: QK-RMSNorm + RoPE + KV append
+    hipLaunchKernelGGL(qk_norm_rope_append_kernel<float>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
+                       inv_freq, (float*)kc, (float*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
+                       dev_state(c), sel, offset, r);
+    // a4: split-K GQA attention + merge
+    if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
+  }
   // a5: O projection + residual
   a = GemvArgs{};
   a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
@@ -506,13 +548,20 @@ bool kv_is_large(const dmtd_ctx* c, int ctx) {
   return bytes > ((size_t)48 << 20);
 }
 
+constexpr int kFusedAttnMaxCtx = 256;    // up to this context one block per (sequence, KV head, row) walks all keys in at most two iterations
+
+void choose_attention(dmtd_ctx* c, int ctx) {
+  c->att_fused = ctx <= kFusedAttnMaxCtx;
+  c->share_kv = !c->att_fused && kv_is_large(c, ctx);
+}
+
 int run_step(dmtd_ctx* c, const Step& s, int n_late) {
-  c->share_kv = kv_is_large(c, s.pos + 1);
+  choose_attention(c, s.pos + 1);
   if (!c->cfg.use_graphs) {
     HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->share_kv ? 1 : 0);
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->att_fused ? 2 : (c->share_kv ? 1 : 0));
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -544,7 +593,7 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
   int r_last = 0, p_last = 0;
   for (int p0 = 0; p0 < P; p0 += kPrefillChunk) {
     const int r = P - p0 < kPrefillChunk ? P - p0 : kPrefillChunk;
-    c->share_kv = kv_is_large(c, p0 + r);
+    choose_attention(c, p0 + r);
     if ((e = embed_rows(c, front, POS_EXPLICIT, p0, r, 0)) != hipSuccess) return e;
     for (int l = 0; l < cf.n_layers; ++l) {
       if (l == add_at && (e = add_embed_rows(c, front, POS_EXPLICIT, p0, r, l)) != hipSuccess) return e;
@@ -569,6 +618,8 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     // attention for `rows` query rows per sequence ending at the newest cached position
     const int last = c->sched.n_tok - 1;
     const int r = rows <= last + 1 ? rows : 1;
+    // the split + merge kernels only: they leave the cache untouched (the fused kernel appends, so it is not timed here)
+    c->share_kv = kv_is_large(c, last + 1);
     if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
     return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
   }
