@@ -43,6 +43,11 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--counters-run", action="store_true",
+                    help="short run for rocprofv3 --pmc: 64-token prompt, DMTD leg only, no kernel timing (counter "
+                         "collection serialises every dispatch); prints no benchmark line")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 1 GiB device copies first (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -57,8 +62,18 @@ def main():
         print("bench.py: no GPU visible; the decode path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB per launch
+        torch.cuda.synchronize()
+        del src, dst
+
     wl = di.WORKLOADS[args.workload]
     sh, B, P, tau, n_late = wl.shape, wl.batch, wl.prompt_len, wl.tau, wl.n_late
+    if args.counters_run:
+        P = 64
     K, W = args.steps, args.warmup
     t0 = time.time()
     blob = di.make_weight_blob(sh, seed=0)
@@ -86,6 +101,9 @@ def main():
         return ntok, dt, ctx0
 
     ntok, dt, ctx0 = run(tau, K, W)
+    if args.counters_run:
+        print(f"counters run done: {ntok} tokens", file=sys.stderr)
+        return
     # tau = 1 on the same kernels, over the same number of tokens
     ntok1, dt1, _ = run(1, K * tau, W * tau)
 
@@ -106,9 +124,10 @@ def main():
         per[f"{kind}_m{r}"] = eng.time_kernel(kind, r, reps)
     gu_bytes = 2 * sh.intermediate * sh.hidden * sh.elem_bytes + sh.hidden * sh.elem_bytes
     achieved = gu_bytes / (per[f"gateup_m{rows}"] * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": f"gemv_kernel<bf16, M={rows}, SWIGLU, NORM> (RMSNorm + gate/up + SwiGLU)",
+    traffic = measured_traffic(args.workload)
+    roofline = {"bound": "hbm", "kernel": f"gemv_mfma_kernel<SWIGLU, NORM> with {rows} rows (RMSNorm + gate/up + SwiGLU)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": gu_bytes, "avg_launch_us": round(per[f"gateup_m{rows}"], 2),
                 "other_kernels_us": {k: round(v, 2) for k, v in per.items()}}
 
@@ -129,6 +148,17 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(t_setup, 1),
     }
     print(json.dumps(out))
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
+    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"gateup_swiglu_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            return json.load(f)["traffic_bytes_per_launch"]
+    except Exception:
+        return None
 
 
 def cpu_baseline(di, blob, sh, tau, n_late):
