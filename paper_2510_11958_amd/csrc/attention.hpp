@@ -1,27 +1,27 @@
-// GQA decode attention for gfx950, split over the KV sequence ("split-K") with a
-// deterministic in-kernel merge.
+// GQA decode attention for gfx950, split over the KV sequence ("split-K"), with the
+// QK-RMSNorm, the rotary embedding and the KV-cache append of the new rows folded in.
 //
-// One block = (split, KV head g, sequence b) and all query vectors that share that KV
-// head: r rows x GQ query heads, QV = r*GQ <= QVT.  K and V rows are read straight from
-// HBM into registers with 16-byte per-lane loads: HD/8 lanes cover one key, so a wave
-// load instruction fetches 64/(HD/8) adjacent keys (1 KiB contiguous).  A block iteration
-// covers 4 keys per lane group; each group scores its keys against every query vector
-// (partial dot per lane, summed inside the lane group by shuffles), keeps a running
-// softmax (max shared across the wave by shuffles, sum and output per lane group) and
-// accumulates p*V for the 8 output dims its lanes own.  At the end the lane groups of a
-// wave are summed by shuffles, the 4 waves merge through LDS, and the split's
-// (max, sum, unnormalised output) go to a partials buffer.  A second, small kernel merges
-// the splits in split order (deterministic) and writes the normalised output; the kernel
-// boundary makes the partials visible across the chip without fences or atomics.
+// Two launches per layer.  (1) attn_split_kernel: a block = (key range, row group, KV head,
+// sequence) and the query vectors of that row group that share the KV head (rows x GQ query
+// heads, at most QVT).  Its key range is fixed by the launch (range index x keys per range), so
+// the K/V loads of its first iteration are issued at once, together with the load of the
+// device-resident position and of the raw q/k/v rows; nothing waits on anything else.  K and V
+// rows go straight from HBM into registers with 16-byte per-lane loads: HD/8 lanes cover one key,
+// so a wave load instruction fetches 64/(HD/8) adjacent keys (1 KiB contiguous).  While they fly
+// the block normalises and rotates its query vectors and the launch's new keys (per-head RMSNorm,
+// then RoPE with half-split pairing at the row's absolute position) into LDS; the block whose
+// range holds a new position takes that key and value from LDS (rounded to the cache's type,
+// exactly what later steps read back) and the last row group's block also writes them to the
+// cache.  Scoring: partial dot per lane, summed inside the lane group by shuffles; running softmax
+// with the maximum shared across the wave; p*V accumulated for the 8 output dims a lane owns;
+// lane groups summed by shuffles, the 4 waves through LDS; the range's (max, sum, unnormalised
+// output) go to a partials buffer.  (2) attn_merge_kernel: per (row, KV head, sequence), merges the
+// ranges in order (deterministic) and writes the normalised output; all its loads are issued
+// before the first one is needed.  The kernel boundary makes the partials visible across the chip
+// (fences and same-kernel grid barriers were measured to cost far more on this chip).
 //
-// Rows can be spread over blocks: a block carries QVT/GQ rows, and grid.x enumerates
-// (split, row group).  With a short context the K/V re-reads this causes are cheap (they
-// hit in L2) and the smaller per-block register footprint wins; with a long context the
-// caller picks a larger QVT so that all rows share one pass over K and V.
-//
-// The number of splits is fixed at launch; the keys per split follow from the current
-// context length, which is read from the device state, so a captured launch stays valid
-// as the sequence grows.
+// Keys beyond the current context inside a block's range are loaded (they lie inside the cache
+// allocation) and masked; ranges wholly beyond the context exit early and are skipped by the merge.
 #pragma once
 #include "kernels.hpp"
 
@@ -33,11 +33,6 @@ constexpr int ATT_MAX_SPLITS = 64;
 // Keys a block covers per iteration: 16 lane groups x 4 keys (head_dim 128) or 32 x 4 (head_dim 64).
 template <int HD> struct AttKeysPerIter { static constexpr int value = 4 * (64 / (HD / 8)) * 4; };
 
-// Keys per split for a launch whose last row sees ctx keys (a multiple of the block
-// iteration); the split kernel and the merge kernel must agree on it.
-__device__ __forceinline__ int att_keys_per_split(int ctx, int n_splits, int kpi) {
-  return ((ctx + n_splits - 1) / n_splits + kpi - 1) / kpi * kpi;
-}
 
 // One block iteration of the running softmax: 4 keys per lane group (kf, vf: this lane's 8 dims of
 // each), scored against every query vector.  After the in-group reduction lane slice sl holds the
@@ -117,10 +112,12 @@ __device__ __forceinline__ void attn_wave_totals(float (&l)[QVT], float (&acc)[Q
 }
 
 template <typename CT, int HD, int QVT>
-__global__ void __launch_bounds__(256) attn_decode_kernel(
-    const float* __restrict__ qkv, int ldq, const CT* __restrict__ kc, const CT* __restrict__ vc,
-    float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, int n_splits, int qv_stride,
-    const DevState* st, int sel, int offset, int r_total) {
+__global__ void __launch_bounds__(256) attn_split_kernel(
+    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
+    const double* __restrict__ inv_freq, CT* __restrict__ kc, CT* __restrict__ vc,
+    float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
+    int kps /* keys per range, a multiple of the block iteration */, int n_splits, int qv_stride,
+    const DevState* st, int sel, int offset, int r_total, int do_append /* 0: leave the cache untouched (measurement) */) {
   typedef typename Elem<CT>::Raw Raw;
   constexpr int LPK = HD / 8;          // lanes per key (16 or 8)
   constexpr int GPW = 64 / LPK;        // lane groups per wave (4 or 8)
@@ -129,6 +126,7 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
   constexpr int KPI = NG * U;          // keys per block iteration
   static_assert(KPI == AttKeysPerIter<HD>::value, "block iteration size");
   constexpr int USH = LPK == 16 ? 2 : 1;   // after the score reduction, lane slice sl holds key u = sl >> USH
+  constexpr int NEW_MAX = 16;          // rows a launch can carry
 
   const int g = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -137,181 +135,51 @@ __global__ void __launch_bounds__(256) attn_decode_kernel(
   const int n_rg = (r_total + rpb - 1) / rpb;
   const int split = blockIdx.x / n_rg, rg = blockIdx.x % n_rg;
   const int r = min(rpb, r_total - rg * rpb), QV = r * GQ;
-  const int pos_first = row_base(st, sel, offset);
-  const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
-  const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
-  const int kps = att_keys_per_split(pos_first + r_total, n_splits, KPI);
-  const int key_begin = split * kps, key_end = min(ctx, key_begin + kps);
-  const float scale = rsqrtf((float)HD);
-
-  __shared__ float wacc[4][QVT][HD];
-  __shared__ float wm[4][QVT], wl[4][QVT];
-
-  // partials are indexed by the launch-wide query-vector number row * GQ + head
-  const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
-  float* my_o = part_o + slot * HD;
-  float* my_ml = part_ml + slot * 2;
-
-  if (key_begin < ctx) {
-    const int sl = lane % LPK, grp = wave * GPW + lane / LPK;
-    const int my_u = sl >> USH;
-    float q[QVT][8];
-#pragma unroll
-    for (int qv = 0; qv < QVT; ++qv) {
-      if (qv < QV) {
-        const float* qp = qkv + (size_t)(b * r_total + rg * rpb + qv / GQ) * ldq + (size_t)(g * GQ + qv % GQ) * HD + sl * 8;
-        const float4 qa = *(const float4*)qp, qb = *(const float4*)(qp + 4);
-        q[qv][0] = qa.x * scale; q[qv][1] = qa.y * scale; q[qv][2] = qa.z * scale; q[qv][3] = qa.w * scale;
-        q[qv][4] = qb.x * scale; q[qv][5] = qb.y * scale; q[qv][6] = qb.z * scale; q[qv][7] = qb.w * scale;
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) q[qv][e] = 0.f;
-      }
-    }
-    float m[QVT], l[QVT], acc[QVT][8];
-#pragma unroll
-    for (int qv = 0; qv < QVT; ++qv) {
-      m[qv] = -INFINITY; l[qv] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[qv][e] = 0.f;
-    }
-    const CT* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
-    const CT* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
-
-    for (int it0 = key_begin; it0 < key_end; it0 += KPI) {
-      float kf[U][8], vf[U][8];
-      {
-        Raw kr[U], vr[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int key = it0 + u * NG + grp;
-          const bool ok = key < key_end;
-          kr[u] = ok ? Elem<CT>::load_raw(kbase + (size_t)key * HD) : Elem<CT>::zero_raw();
-          vr[u] = ok ? Elem<CT>::load_raw(vbase + (size_t)key * HD) : Elem<CT>::zero_raw();
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) { Elem<CT>::unpack(kr[u], kf[u]); Elem<CT>::unpack(vr[u], vf[u]); }
-      }
-      const int my_key = it0 + my_u * NG + grp;       // the key whose score this lane will hold
-      attn_accumulate<HD, QVT>(q, kf, vf, my_key, key_end, pos0, GQ, QV, lane, sl, m, l, acc);
-    }
-
-    attn_wave_totals<HD, QVT>(l, acc);
-    if (lane < LPK) {
-#pragma unroll
-      for (int qv = 0; qv < QVT; ++qv)
-        if (qv < QV) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) wacc[wave][qv][sl * 8 + e] = acc[qv][e];
-          if (lane == 0) { wm[wave][qv] = m[qv]; wl[wave][qv] = l[qv]; }
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < QV * HD; e += 256) {
-      const int qv = e / HD, d = e % HD;
-      const float mm = fmaxf(fmaxf(wm[0][qv], wm[1][qv]), fmaxf(wm[2][qv], wm[3][qv]));
-      float o = 0.f, ll = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
-        o += f * wacc[w][qv][d];
-        ll += f * wl[w][qv];
-      }
-      my_o[qv * HD + d] = o;
-      if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
-    }
-  }
-
-}
-
-// Merge the splits' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
-// f_s = exp(m_s - max_s m_s), splits taken in order.  One block per (row, KV head, sequence).
-template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection)
-__global__ void __launch_bounds__(256) attn_merge_kernel(
-    const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, int ldo,
-    int nh, int nkv, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
-  const int i = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x;
-  const int GQ = nh / nkv;
-  const int pos_first = row_base(st, sel, offset);
-  const int kps = att_keys_per_split(pos_first + r_total, n_splits, AttKeysPerIter<HD>::value);
-  const int n_act = (pos_first + i + 1 + kps - 1) / kps;          // splits that hold keys visible to row i
-  __shared__ float f_s[ATT_MAX_SPLITS][QV_MAX];
-  __shared__ float inv_l[QV_MAX];
-  const size_t slot0 = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
-  for (int e = tid; e < n_act * GQ; e += 256) {
-    const int s2 = e / GQ, j = e % GQ;
-    f_s[s2][j] = part_ml[((slot0 + s2) * qv_stride + i * GQ + j) * 2];
-  }
-  __syncthreads();
-  if (tid < GQ) {
-    float mm = -INFINITY;
-    for (int s2 = 0; s2 < n_act; ++s2) mm = fmaxf(mm, f_s[s2][tid]);
-    float ll = 0.f;
-    for (int s2 = 0; s2 < n_act; ++s2) {
-      const float f = (f_s[s2][tid] == -INFINITY) ? 0.f : __expf(f_s[s2][tid] - mm);
-      ll += f * part_ml[((slot0 + s2) * qv_stride + i * GQ + tid) * 2 + 1];
-      f_s[s2][tid] = f;
-    }
-    inv_l[tid] = 1.0f / ll;
-  }
-  __syncthreads();
-  for (int e = tid; e < GQ * HD; e += 256) {
-    const int j = e / HD, d = e % HD;
-    const float* po = part_o + ((slot0 * qv_stride) + i * GQ + j) * HD + d;
-    float o = 0.f;
-#pragma unroll 8
-    for (int s2 = 0; s2 < n_act; ++s2) {
-      const float f = f_s[s2][j];
-      const float v = po[(size_t)s2 * qv_stride * HD];
-      o += (f == 0.f) ? 0.f : f * v;      // splits without visible keys hold stale partials: weight 0, value ignored
-    }
-    out[(size_t)(b * r_total + i) * ldo + (size_t)(g * GQ + j) * HD + d] = Elem<OT>::from_f32(o * inv_l[j]);
-  }
-}
-
-// Short-context variant: ONE kernel per layer does QK-RMSNorm + RoPE of the new rows, the KV-cache
-// append, the whole attention over the sequence and the normalisation.  A block is (row group,
-// KV head, sequence) and walks all keys itself with NW waves, so there is no split to merge and
-// nothing another block must see: the new keys and values are formed in LDS from the raw
-// projections (rounded to the cache's type, exactly what later steps will read back) and the
-// last row group's block also writes them to the cache.  Used while the K/V of a sequence is
-// small enough that a handful of blocks can pull it without starving the chip.
-template <typename CT, typename OT, int HD, int QVT, int NW>
-__global__ void __launch_bounds__(64 * NW) attn_fused_kernel(
-    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
-    const double* __restrict__ inv_freq, CT* __restrict__ kc, CT* __restrict__ vc, OT* __restrict__ out, int ldo,
-    int nh, int nkv, int s_max, float eps, const DevState* st, int sel, int offset, int r_total) {
-  typedef typename Elem<CT>::Raw Raw;
-  constexpr int LPK = HD / 8, GPW = 64 / LPK, NG = NW * GPW, U = 4, KPI = NG * U;
-  constexpr int USH = LPK == 16 ? 2 : 1;
-  constexpr int NEW_MAX = 16;                                   // rows a launch can carry
-  const int rg = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int GQ = nh / nkv, rpb = QVT / GQ;
-  const int r = min(rpb, r_total - rg * rpb), QV = r * GQ;
-  const int pos_first = row_base(st, sel, offset);
-  const int pos0 = pos_first + rg * rpb, ctx = pos0 + r;
-  const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
-  const bool writer = (rg + 1) * rpb >= r_total;                // the last row group's block appends to the cache
-  const float scale = rsqrtf((float)HD);
+  const int key_begin = split * kps;
+  const int sl = lane % LPK, grp = wave * GPW + lane / LPK;
+  const int my_u = sl >> USH;
 
   __shared__ float q_s[QVT][HD];
   __shared__ float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
-  __shared__ float wacc[NW][QVT][HD];
-  __shared__ float wm[NW][QVT], wl[NW][QVT];
+  __shared__ float wacc[4][QVT][HD];
+  __shared__ float wm[4][QVT], wl[4][QVT];
 
-  // ---- prologue: per-head RMSNorm + RoPE (pair (i, i + HD/2)) of this block's queries and of the new keys
+  // K/V of the first iteration: addresses depend on the launch only
+  const CT* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
+  const CT* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
+  Raw kr[U], vr[U];
+  auto load_kv = [&](int it0, int limit) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int key = it0 + u * NG + grp;
+      const bool ok = key < limit;
+      kr[u] = ok ? Elem<CT>::load_raw(kbase + (size_t)key * HD) : Elem<CT>::zero_raw();
+      vr[u] = ok ? Elem<CT>::load_raw(vbase + (size_t)key * HD) : Elem<CT>::zero_raw();
+    }
+  };
+  load_kv(key_begin, min(s_max, key_begin + kps));
+
+  const int pos_first = row_base(st, sel, offset);
+  const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
+  const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
+  if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
+  const int key_end = min(ctx, key_begin + kps);
+  const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
+  const bool holds_new = key_end > pos_first;                   // a new position falls into this range
+  const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
+  const float scale = rsqrtf((float)HD);
+
+  // ---- per-head RMSNorm + RoPE (pair (i, i + HD/2)) of this block's queries and, where needed, of the new keys
   {
     constexpr int half = HD / 2;
     const bool act = lane < half;
-    const int n_vec = QV + 2 * n_new;                           // queries, new keys, new values
-    for (int v = wave; v < n_vec; v += NW) {
+    const int n_vec = QV + (holds_new ? 2 * n_new : 0);         // queries, new keys, new values
+    for (int v = wave; v < n_vec; v += 4) {
       if (v < QV + n_new) {
         const bool is_q = v < QV;
         const int row = is_q ? rg * rpb + v / GQ : v - QV;      // row of the launch
-        const int head = is_q ? g * GQ + v % GQ : nh + g;
-        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)head * HD;
+        const int hcol = is_q ? g * GQ + v % GQ : nh + g;
+        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD;
         float x0 = act ? src[lane] : 0.f, x1 = act ? src[lane + half] : 0.f;
         const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)HD + eps);
         if (act) {
@@ -327,28 +195,28 @@ __global__ void __launch_bounds__(64 * NW) attn_fused_kernel(
           } else {
             const CT c0 = Elem<CT>::from_f32(y0), c1 = Elem<CT>::from_f32(y1);
             knew_s[row][lane] = Elem<CT>::to_f32(c0); knew_s[row][lane + half] = Elem<CT>::to_f32(c1);
-            if (writer) {
-              CT* dst = kc + (((size_t)b * nkv + g) * s_max + pos_first + row) * HD;
+            const int key = pos_first + row;
+            if (writer && key >= key_begin && key < key_end) {
+              CT* dst = kc + (((size_t)b * nkv + g) * s_max + key) * HD;
               dst[lane] = c0; dst[lane + half] = c1;
             }
           }
         }
       } else {
-        const int row = v - QV - n_new;
+        const int row = v - QV - n_new, key = pos_first + row;
         const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)(nh + nkv + g) * HD;
-        CT* dst = vc + (((size_t)b * nkv + g) * s_max + pos_first + row) * HD;
+        CT* dst = vc + (((size_t)b * nkv + g) * s_max + key) * HD;
+        const bool wr = writer && key >= key_begin && key < key_end;
         for (int k = lane; k < HD; k += 64) {
           const CT cv = Elem<CT>::from_f32(src[k]);
           vnew_s[row][k] = Elem<CT>::to_f32(cv);
-          if (writer) dst[k] = cv;
+          if (wr) dst[k] = cv;
         }
       }
     }
   }
   __syncthreads();
 
-  const int sl = lane % LPK, grp = wave * GPW + lane / LPK;
-  const int my_u = sl >> USH;
   float q[QVT][8];
 #pragma unroll
   for (int qv = 0; qv < QVT; ++qv)
@@ -361,39 +229,24 @@ __global__ void __launch_bounds__(64 * NW) attn_fused_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[qv][e] = 0.f;
   }
-  const CT* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
-  const CT* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD + sl * 8;
 
-  // ---- cached keys 0 .. pos_first-1 (all visible to every row of the block)
-  for (int it0 = 0; it0 < pos_first; it0 += KPI) {
+  for (int it0 = key_begin; it0 < key_end; it0 += KPI) {
     float kf[U][8], vf[U][8];
-    {
-      Raw kr[U], vr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) { Elem<CT>::unpack(kr[u], kf[u]); Elem<CT>::unpack(vr[u], vf[u]); }
+    if (it0 + KPI < key_end) load_kv(it0 + KPI, key_end);       // next iteration's keys fly during the scoring
+    if (holds_new) {
+      // new positions: key and value come from LDS, not from the cache slot (written by another block, or not yet)
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int key = it0 + u * NG + grp;
-        const bool ok = key < pos_first;
-        kr[u] = ok ? Elem<CT>::load_raw(kbase + (size_t)key * HD) : Elem<CT>::zero_raw();
-        vr[u] = ok ? Elem<CT>::load_raw(vbase + (size_t)key * HD) : Elem<CT>::zero_raw();
-      }
+        const int i = it0 + u * NG + grp - pos_first;
+        if (i >= 0 && i < n_new) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) { Elem<CT>::unpack(kr[u], kf[u]); Elem<CT>::unpack(vr[u], vf[u]); }
-    }
-    attn_accumulate<HD, QVT>(q, kf, vf, it0 + my_u * NG + grp, pos_first, pos0, GQ, QV, lane, sl, m, l, acc);
-  }
-  // ---- the new keys pos_first .. ctx-1, from LDS (one iteration: n_new <= 16 <= KPI)
-  {
-    float kf[U][8], vf[U][8];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int i = u * NG + grp;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        kf[u][e] = i < n_new ? knew_s[i][sl * 8 + e] : 0.f;
-        vf[u][e] = i < n_new ? vnew_s[i][sl * 8 + e] : 0.f;
+          for (int e = 0; e < 8; ++e) { kf[u][e] = knew_s[i][sl * 8 + e]; vf[u][e] = vnew_s[i][sl * 8 + e]; }
+        }
       }
     }
-    attn_accumulate<HD, QVT>(q, kf, vf, pos_first + my_u * NG + grp, ctx, pos0, GQ, QV, lane, sl, m, l, acc);
+    attn_accumulate<HD, QVT>(q, kf, vf, it0 + my_u * NG + grp, key_end, pos0, GQ, QV, lane, sl, m, l, acc);
   }
 
   attn_wave_totals<HD, QVT>(l, acc);
@@ -407,19 +260,84 @@ __global__ void __launch_bounds__(64 * NW) attn_fused_kernel(
       }
   }
   __syncthreads();
-  for (int e = tid; e < QV * HD; e += 64 * NW) {
+  // partials are indexed by the launch-wide query-vector number row * GQ + head
+  const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
+  float* my_o = part_o + slot * HD;
+  float* my_ml = part_ml + slot * 2;
+  for (int e = tid; e < QV * HD; e += 256) {
     const int qv = e / HD, d = e % HD;
-    float mm = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) mm = fmaxf(mm, wm[w][qv]);
+    const float mm = fmaxf(fmaxf(wm[0][qv], wm[1][qv]), fmaxf(wm[2][qv], wm[3][qv]));
     float o = 0.f, ll = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < 4; ++w) {
       const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
       o += f * wacc[w][qv][d];
       ll += f * wl[w][qv];
     }
-    out[(size_t)(b * r_total + rg * rpb + qv / GQ) * ldo + (size_t)(g * GQ + qv % GQ) * HD + d] = Elem<OT>::from_f32(o / ll);
+    my_o[qv * HD + d] = o;
+    if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
+  }
+}
+
+// Merge the ranges' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
+// f_s = exp(m_s - max_s m_s), ranges taken in order.  One block (128 threads) per (row, query head,
+// sequence); every load is issued before the first one is needed.
+template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection)
+__global__ void __launch_bounds__(128) attn_merge_kernel(
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, int ldo,
+    int nh, int nkv, int kps, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
+  constexpr int PRE = 32;                 // ranges whose partials a thread fetches before anything is waited for
+  const int i = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int GQ = nh / nkv, g = head / GQ, j = head % GQ;
+  __shared__ float f_s[ATT_MAX_SPLITS], l_s[ATT_MAX_SPLITS];
+  __shared__ float mm_s, inv_l_s;
+  const size_t slot0 = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
+  const size_t qv = (size_t)i * GQ + j;
+  float mv = -INFINITY, lv = 0.f;
+  if (tid < n_splits) {
+    const float* p = part_ml + ((slot0 + tid) * qv_stride + qv) * 2;
+    mv = p[0]; lv = p[1];
+  }
+  float ov[PRE];
+#pragma unroll
+  for (int s2 = 0; s2 < PRE; ++s2)
+    ov[s2] = (tid < HD && s2 < n_splits) ? part_o[((slot0 + s2) * qv_stride + qv) * HD + tid] : 0.f;
+  const int pos_row = row_base(st, sel, offset) + i;    // row i sees keys 0 .. pos_row
+  const int n_act = min(n_splits, pos_row / kps + 1);   // ranges that hold keys visible to row i; later ones hold stale partials
+  if (tid < ATT_MAX_SPLITS) f_s[tid] = (tid < n_act) ? mv : -INFINITY;
+  __syncthreads();
+  if (tid == 0) {
+    float mm = -INFINITY;
+    for (int s2 = 0; s2 < n_act; ++s2) mm = fmaxf(mm, f_s[s2]);
+    mm_s = mm;
+  }
+  __syncthreads();
+  if (tid < ATT_MAX_SPLITS) {
+    const float f = (tid < n_act && mv != -INFINITY) ? __expf(mv - mm_s) : 0.f;
+    f_s[tid] = f;
+    l_s[tid] = f * lv;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float ll = 0.f;
+    for (int s2 = 0; s2 < n_act; ++s2) ll += l_s[s2];
+    inv_l_s = 1.0f / ll;
+  }
+  __syncthreads();
+  if (tid < HD) {
+    float o = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < PRE; ++s2) {
+      const float f = s2 < n_act ? f_s[s2] : 0.f;
+      o += (f == 0.f) ? 0.f : f * ov[s2];
+    }
+    for (int s2 = PRE; s2 < n_act; ++s2) {
+      const float f = f_s[s2];
+      const float v = part_o[((slot0 + s2) * qv_stride + qv) * HD + tid];
+      o += (f == 0.f) ? 0.f : f * v;
+    }
+    out[(size_t)(b * r_total + i) * ldo + (size_t)head * HD + tid] = Elem<OT>::from_f32(o * inv_l_s);
   }
 }
 

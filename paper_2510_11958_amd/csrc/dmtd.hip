@@ -81,7 +81,7 @@ struct dmtd_ctx {
   std::vector<LayerSw> sw;
   std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
-  bool att_fused = false;     // attention launches: the fused short-context kernel
+  int att_bucket = 512;       // attention launches: context bucket (multiple of 512) the key ranges are laid out for
 };
 
 namespace {
@@ -277,75 +277,54 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
 
 // ------------------------------------------------------------------------- attention
 
+// a3 + a4: QK-RMSNorm, RoPE, KV append and split-K attention in one launch over static key ranges, then the merge.
+// The ranges follow from the context bucket (c->att_bucket, a multiple of 512 that covers the context), so a
+// captured step stays valid until the sequence grows into the next bucket.
 template <typename CT, typename OT, int HD, int QVT>
-void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
+void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r, int append) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
   const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
-  const CT* kc = (const CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
-  const CT* vc = (const CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
-  // enough splits to put about two blocks on every CU, whatever the batch
-  int ns = 2 * c->num_cus / (cf.n_kv_heads * B * n_rg);
-  if (ns > ATT_MAX_SPLITS) ns = ATT_MAX_SPLITS;
-  if (ns < 1) ns = 1;
+  constexpr int KPI = AttKeysPerIter<HD>::value;
+  CT* kc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  CT* vc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  const LayerW& w = c->layers[l];
+  // keys per range: one block iteration while that keeps the ranges within the partials buffer and puts no
+  // more than about four blocks on every CU; longer ranges (several iterations) for long contexts or big batches
+  const int bucket = c->att_bucket;
+  long per_split_blocks = (long)cf.n_kv_heads * B * n_rg;
+  int want_splits = (int)((4L * c->num_cus + per_split_blocks - 1) / per_split_blocks);
+  if (want_splits > ATT_MAX_SPLITS) want_splits = ATT_MAX_SPLITS;
+  if (want_splits < 1) want_splits = 1;
+  int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
+  const int ns = (bucket + kps - 1) / kps;
   float* po = (float*)(c->ws + c->o.part_o);
   float* pml = (float*)(c->ws + c->o.part_ml);
   const DevState* st = dev_state(c);
-  hipLaunchKernelGGL((attn_decode_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
-                     kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, ns, kMaxRows * gq, st, sel, offset, r);
-  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_kv_heads, B), dim3(256), 0, c->stream, po, pml, attn, qd,
-                     cf.n_q_heads, cf.n_kv_heads, ns, kMaxRows * gq, st, sel, offset, r);
+  hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
+                     w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
+                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, qd,
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
 }
 
 // share_kv: all rows of a sequence go through one block so that K and V are read once
 // (long contexts); otherwise rows are spread over blocks (short contexts, K/V re-reads hit in L2).
 template <typename CT, typename OT>
-hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
+hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r, int append = 1) {
   const dmtd_config& cf = c->cfg;
   const int gq = cf.n_q_heads / cf.n_kv_heads;
   if (r > kMaxRows) return hipErrorInvalidValue;
   const int want = c->share_kv ? r * gq : gq;
   const int qvt = want <= 4 ? 4 : (want <= 8 ? 8 : 16);
   if (cf.head_dim == 128) {
-    if (qvt == 4) launch_attention_t<CT, OT, 128, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_t<CT, OT, 128, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_t<CT, OT, 128, 16>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<CT, OT, 128, 4>(c, l, qkv, attn, sel, offset, r, append);
+    else if (qvt == 8) launch_attention_t<CT, OT, 128, 8>(c, l, qkv, attn, sel, offset, r, append);
+    else launch_attention_t<CT, OT, 128, 16>(c, l, qkv, attn, sel, offset, r, append);
   } else {
-    if (qvt == 4) launch_attention_t<CT, OT, 64, 4>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_t<CT, OT, 64, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_t<CT, OT, 64, 16>(c, l, qkv, attn, sel, offset, r);
-  }
-  return hipGetLastError();
-}
-
-// Short contexts: one kernel does QK-norm, RoPE, the cache append and the whole attention (no split, no merge).
-template <typename CT, typename OT, int HD, int QVT, int NW>
-void launch_attention_fused_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
-  const dmtd_config& cf = c->cfg;
-  const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
-  const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
-  const LayerW& w = c->layers[l];
-  CT* kc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
-  CT* vc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
-  hipLaunchKernelGGL((attn_fused_kernel<CT, OT, HD, QVT, NW>), dim3(n_rg, cf.n_kv_heads, c->batch), dim3(64 * NW), 0, c->stream,
-                     qkv, nqkv, w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, attn, qd, cf.n_q_heads,
-                     cf.n_kv_heads, cf.max_seq_len, cf.rms_eps, dev_state(c), sel, offset, r);
-}
-
-template <typename CT, typename OT>
-hipError_t launch_attention_fused(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r) {
-  const dmtd_config& cf = c->cfg;
-  const int gq = cf.n_q_heads / cf.n_kv_heads;
-  if (r > kMaxRows) return hipErrorInvalidValue;
-  const int qvt = gq <= 4 ? 4 : (gq <= 8 ? 8 : 16);      // one row (or a few, for small groups) per block
-  if (cf.head_dim == 128) {
-    if (qvt == 4) launch_attention_fused_t<CT, OT, 128, 4, 8>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_fused_t<CT, OT, 128, 8, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_fused_t<CT, OT, 128, 16, 4>(c, l, qkv, attn, sel, offset, r);
-  } else {
-    if (qvt == 4) launch_attention_fused_t<CT, OT, 64, 4, 8>(c, l, qkv, attn, sel, offset, r);
-    else if (qvt == 8) launch_attention_fused_t<CT, OT, 64, 8, 8>(c, l, qkv, attn, sel, offset, r);
-    else launch_attention_fused_t<CT, OT, 64, 16, 4>(c, l, qkv, attn, sel, offset, r);
+    if (qvt == 4) launch_attention_t<CT, OT, 64, 4>(c, l, qkv, attn, sel, offset, r, append);
+    else if (qvt == 8) launch_attention_t<CT, OT, 64, 8>(c, l, qkv, attn, sel, offset, r, append);
+    else launch_attention_t<CT, OT, 64, 16>(c, l, qkv, attn, sel, offset, r, append);
   }
   return hipGetLastError();
 }
@@ -406,10 +385,6 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * hd, qd = cf.n_q_heads * hd;
   float* qkv = (float*)(c->ws + c->o.qkv);
   const LayerW& w = c->layers[l];
-  char* kc = c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride;
-  char* vc = kc + c->o.kv_v_off;
-  const double* inv_freq = (const double*)(c->ws + c->o.inv_freq);
-  const dim3 rope_grid(cf.n_q_heads + 2 * cf.n_kv_heads, rows);
   hipError_t e;
   if (c->packed) {
     const LayerSw& s = c->sw[l];
@@ -421,17 +396,8 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
     a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
     if ((e = launch_mfma<EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
-    if (c->att_fused) {
-      // a3 + a4 in one kernel (short contexts): QK-RMSNorm + RoPE + KV append + attention, packed output
-      if ((e = launch_attention_fused<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
-    } else {
-      // a3: QK-RMSNorm + RoPE + KV append
-      hipLaunchKernelGGL(qk_norm_rope_append_kernel<bf16_t>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
-                         inv_freq, (bf16_t*)kc, (bf16_t*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
-                         dev_state(c), sel, offset, r);
-      // a4: split-K GQA attention + merge (output packed for the O projection)
-      if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
-    }
+    // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge (output packed for the O projection)
+    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
     // a5: O projection + residual; emits the MLP norm's input
     a = MfmaArgs{};
     a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
@@ -458,16 +424,8 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   // a2: RMSNorm + fused QKV projection (q, k, v are contiguous in the blob)
   a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
   if ((e = gemv_rows<float, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
-  if (c->att_fused) {
-    if ((e = launch_attention_fused<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
-  } else {
-    // a3: QK-RMSNorm + RoPE + KV append
-    hipLaunchKernelGGL(qk_norm_rope_append_kernel<float>, rope_grid, dim3(64), 0, c->stream, qkv, nqkv, w.q_norm, w.k_norm,
-                       inv_freq, (float*)kc, (float*)vc, cf.n_q_heads, cf.n_kv_heads, hd, cf.max_seq_len, cf.rms_eps,
-                       dev_state(c), sel, offset, r);
-    // a4: split-K GQA attention + merge
-    if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
-  }
+  // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge
+  if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
   // a5: O projection + residual
   a = GemvArgs{};
   a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
@@ -503,7 +461,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
     e = gemv_rows<float, EPI_LOGITS, true>(c, a, n_rows);
   }
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(64), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
+  hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(n_rows >= 16 ? 1024 : 64 * n_rows), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
                      dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens);
   return hipGetLastError();
 }
@@ -548,11 +506,9 @@ bool kv_is_large(const dmtd_ctx* c, int ctx) {
   return bytes > ((size_t)48 << 20);
 }
 
-constexpr int kFusedAttnMaxCtx = 256;    // up to this context one block per (sequence, KV head, row) walks all keys in at most two iterations
-
 void choose_attention(dmtd_ctx* c, int ctx) {
-  c->att_fused = ctx <= kFusedAttnMaxCtx;
-  c->share_kv = !c->att_fused && kv_is_large(c, ctx);
+  c->att_bucket = (ctx + 511) / 512 * 512;
+  c->share_kv = kv_is_large(c, ctx);
 }
 
 int run_step(dmtd_ctx* c, const Step& s, int n_late) {
@@ -561,7 +517,7 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
     HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->att_fused ? 2 : (c->share_kv ? 1 : 0));
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->att_bucket * 2 + (c->share_kv ? 1 : 0));
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -618,10 +574,10 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     // attention for `rows` query rows per sequence ending at the newest cached position
     const int last = c->sched.n_tok - 1;
     const int r = rows <= last + 1 ? rows : 1;
-    // the split + merge kernels only: they leave the cache untouched (the fused kernel appends, so it is not timed here)
-    c->share_kv = kv_is_large(c, last + 1);
-    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
-    return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r);
+    // the cache append is switched off: the launch scores the rows' new keys from the scratch q/k/v, writes nothing
+    choose_attention(c, last + 1);
+    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r, 0);
+    return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r, 0);
   }
   if (kind == DMTD_K_LMHEAD) {
     R.n_parts = 1;

@@ -132,6 +132,18 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
     }
   };
   load_a(s0);                                             // the weight stream starts before anything waits
+  // residual epilogue: this thread's residual value and next-norm gain, fetched now so the epilogue does not wait
+  constexpr int EPN = (256 + NT - 1) / NT;
+  float hpre[EPN], gpre[EPN];
+  if (EPI == EPI_RESID) {
+#pragma unroll
+    for (int q = 0; q < EPN; ++q) {
+      const int t = tid + q * NT, c = t >> 4, n = tile * 16 + (t & 15);
+      const bool ok = t < 256 && c < M && n < N;
+      hpre[q] = ok ? a.y[(size_t)c * a.ldy + n] : 0.f;
+      gpre[q] = ok ? bf16_to_f32(a.g_next[n]) : 0.f;
+    }
+  }
   if (NORM) {
     // the producer's partial sums of squares, M * n_parts floats, fetched by all threads while the weights fly
     const int n_items = M * a.n_parts;
@@ -211,7 +223,10 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
     __syncthreads();
   }
 
-  for (int t = tid; t < 256; t += 64 * NWT) {
+#pragma unroll
+  for (int q = 0; q < EPN; ++q) {
+    const int t = tid + q * NT;
+    if (t >= 256) break;
     const int c = t >> 4, row = t & 15, n = tile * 16 + row;
     float hsq = 0.f;
     if (c < M && n < N) {
@@ -227,11 +242,10 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
         v1 *= rs;
         a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(v0 / (1.0f + __expf(-v0)) * v1);
       } else if (EPI == EPI_RESID) {
-        float* dst = a.y + (size_t)c * a.ldy + n;
-        const float hn = *dst + v0;
-        *dst = hn;
+        const float hn = hpre[q] + v0;
+        a.y[(size_t)c * a.ldy + n] = hn;
         hsq = hn * hn;
-        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(hn * bf16_to_f32(a.g_next[n]));
+        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(hn * gpre[q]);
       } else {
         a.y[(size_t)c * a.ldy + n] = v0;
         if (EPI == EPI_LOGITS) atomicMax(&key_s[c], argmax_key(v0, n));

@@ -126,18 +126,23 @@ __device__ __forceinline__ int argmax_key_index(unsigned long long key) { return
 // output slot and, unless the caller forces the next input, to the token history), clear the
 // keys, and advance the state: one more token is in the late caches; a full step also closes
 // the refill gap.  With write_tokens == 0 only the keys are cleared (measurement launches).
-__global__ void finish_step_kernel(DevState* st, unsigned long long* amax, int n_cells, int amax_ld, int* tokens, int* emitted,
-                                   int s_max, int batch, int full, int write_tokens) {
+__global__ void __launch_bounds__(1024) finish_step_kernel(DevState* st, unsigned long long* amax, int n_cells /* <= 64 */, int amax_ld,
+                                                           int* tokens, int* emitted, int s_max, int batch, int full, int write_tokens) {
   const int pos = st->n_tok, step = st->step_idx, forced_until = st->forced_until;
-  for (int b = threadIdx.x; b < batch; b += blockDim.x) {
-    unsigned long long best = 0ull;      // keys are spread over n_cells cells per sequence
-    for (int c = 0; c < n_cells; ++c) {
-      const unsigned long long k = amax[(size_t)c * amax_ld + b];
-      if (k > best) best = k;
-      amax[(size_t)c * amax_ld + b] = 0ull;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+  for (int b = wave; b < batch; b += n_waves) {      // one wave per sequence; lane = cell (keys are spread over n_cells cells)
+    unsigned long long best = 0ull;
+    if (lane < n_cells) {
+      best = amax[(size_t)lane * amax_ld + b];
+      amax[(size_t)lane * amax_ld + b] = 0ull;
     }
-    const int tok = argmax_key_index(best);
-    if (write_tokens) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const unsigned long long other = __shfl_xor(best, o, 64);
+      if (other > best) best = other;
+    }
+    if (lane == 0 && write_tokens) {
+      const int tok = argmax_key_index(best);
       emitted[step * batch + b] = tok;
       if (pos + 1 < s_max && pos + 1 >= forced_until) tokens[(size_t)b * s_max + pos + 1] = tok;
     }
@@ -189,48 +194,6 @@ __global__ void add_embed_rows_kernel(float* __restrict__ h, const WT* __restric
   const WT* e = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* o = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += Elem<WT>::to_f32(e[k]);
-}
-
-// ------------------------------------------- QK-RMSNorm + RoPE + KV-cache append
-//
-// One wave per (row, head).  Query heads: per-head RMSNorm (gain [hd]), rotary embedding
-// with half-split pairing (i, i+hd/2) at the row's absolute position, written back in
-// place.  Key heads: the same, written to the cache slot of that position.  Value
-// heads: copied to the cache.  Angles are formed in double from a host-computed
-// double table of theta^(-2i/hd), so long contexts lose no accuracy.
-template <typename CT>
-__global__ void __launch_bounds__(64) qk_norm_rope_append_kernel(
-    float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
-    const double* __restrict__ inv_freq, CT* __restrict__ kc, CT* __restrict__ vc, int nh, int nkv, int hd,
-    int s_max, float eps, const DevState* st, int sel, int explicit_pos, int r) {
-  const int head = blockIdx.x, row = blockIdx.y, b = row / r, i = row % r;
-  const int pos = row_base(st, sel, explicit_pos) + i;
-  const int lane = threadIdx.x, half = hd >> 1;
-  float* src = qkv + (size_t)row * ldq + (size_t)head * hd;
-  if (head >= nh + nkv) {   // value head: plain copy into the cache
-    const int g = head - nh - nkv;
-    CT* dst = vc + (((size_t)b * nkv + g) * s_max + pos) * hd;
-    for (int k = lane; k < hd; k += 64) dst[k] = Elem<CT>::from_f32(src[k]);
-    return;
-  }
-  const bool act = lane < half;
-  float x0 = act ? src[lane] : 0.f, x1 = act ? src[lane + half] : 0.f;
-  const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)hd + eps);
-  if (!act) return;
-  const CT* g = (const CT*)(head < nh ? q_gain : k_gain);
-  x0 *= rs * Elem<CT>::to_f32(g[lane]);
-  x1 *= rs * Elem<CT>::to_f32(g[lane + half]);
-  double sn, cs;
-  sincos((double)pos * inv_freq[lane], &sn, &cs);
-  const float c = (float)cs, s = (float)sn;
-  const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
-  if (head < nh) {
-    src[lane] = y0; src[lane + half] = y1;
-  } else {
-    const int gk = head - nh;
-    CT* dst = kc + (((size_t)b * nkv + gk) * s_max + pos) * hd;
-    dst[lane] = Elem<CT>::from_f32(y0); dst[lane + half] = Elem<CT>::from_f32(y1);
-  }
 }
 
 }  // namespace dmtd
