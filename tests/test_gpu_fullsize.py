@@ -88,13 +88,21 @@ def test_c3_full_prompt_first_cycles(model_4b):
         s = eng.state()
         assert (s["n_tok"], s["n_front"], s["phase"]) == (orc.n_tok, orc.n_front, orc.phase)
     assert worst < TOL_BF16, worst
-    # cache contents of a front and a late layer
-    for l in (0, sh.n_layers - 1):
+    # Cache contents of the first and the last layer against the oracle's unrounded float32 cache.
+    # Layer 0 carries one bf16 rounding of the stored value plus those of the projection's inputs.
+    # The last layer carries the noise of the 35 bf16 layers before it (measured: it grows roughly with
+    # the square root of the depth, evenly over positions); the maximum is taken over about a million
+    # entries (8 heads x 1032 positions x 128), whose extreme lies near five standard deviations, so
+    # the bounds are 3e-2 of the root mean square and 4e-2 of the largest entry.
+    for l, tol_rms, tol_max in ((0, 4e-3, 6e-3), (sh.n_layers - 1, 3e-2, 4e-2)):
         kv = eng.read_kv(l, 0, orc.n_tok)
         upto = orc.n_tok if l >= sh.n_layers - wl.n_late else orc.n_front
         for which, refc in ((0, orc.K[l]), (1, orc.V[l])):
-            r = np.transpose(refc[:upto], (1, 0, 2))
-            assert np.abs(kv[which][:, :upto] - r).max() / np.abs(r).max() < 2e-2
+            r = np.transpose(refc[:upto], (1, 0, 2)).astype(np.float64)
+            e = kv[which][:, :upto].astype(np.float64) - r
+            e_rms = float(np.sqrt(np.mean(e * e)) / np.sqrt(np.mean(r * r)))
+            e_max = float(np.abs(e).max() / np.abs(r).max())
+            assert e_rms < tol_rms and e_max < tol_max, (l, "KV"[which], e_rms, e_max)
     # whole-cycle calls, free running: tokens are the argmax of the logits the library reports
     for _ in range(6):
         out = eng.decode_cycle(wl.tau, wl.n_late)
