@@ -9,7 +9,7 @@
 // rows go straight from HBM into registers with 16-byte per-lane loads: HD/8 lanes cover one key,
 // so a wave load instruction fetches 64/(HD/8) adjacent keys (1 KiB contiguous).  While they fly
 // the block normalises and rotates its query vectors and the launch's new keys (per-head RMSNorm,
-// then RoPE with half-split pairing at the row's absolute position) into LDS; the block whose
+// then RoPE with half-split pairing at the row's absolute position, cos/sin from a table) into LDS; the block whose
 // range holds a new position takes that key and value from LDS (rounded to the cache's type,
 // exactly what later steps read back) and the last row group's block also writes them to the
 // cache.  Scoring: partial dot per lane, summed inside the lane group by shuffles; running softmax
@@ -111,10 +111,21 @@ __device__ __forceinline__ void attn_wave_totals(float (&l)[QVT], float (&acc)[Q
     }
 }
 
+// Rotary table, built once: (cos, sin) of position * theta^(-2i/hd), angle and functions in double
+// precision, stored rounded to float (what the attention kernel would otherwise compute per launch).
+__global__ void rope_table_kernel(const double* __restrict__ inv_freq, float2* __restrict__ tab, int s_max, int half) {
+  const size_t n = (size_t)s_max * half;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    double sn, cs;
+    sincos((double)(i / half) * inv_freq[i % half], &sn, &cs);
+    tab[i] = make_float2((float)cs, (float)sn);
+  }
+}
+
 template <typename CT, int HD, int QVT>
 __global__ void __launch_bounds__(256) attn_split_kernel(
     const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
-    const double* __restrict__ inv_freq, CT* __restrict__ kc, CT* __restrict__ vc,
+    const float2* __restrict__ rope_tab /* [s_max][HD / 2] (cos, sin) of position * theta^(-2i/HD) */, CT* __restrict__ kc, CT* __restrict__ vc,
     float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
     int kps /* keys per range, a multiple of the block iteration */, int n_splits, int qv_stride,
     const DevState* st, int sel, int offset, int r_total, int do_append /* 0: leave the cache untouched (measurement) */) {
@@ -186,9 +197,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
           const CT* gn = (const CT*)(is_q ? q_gain : k_gain);
           x0 *= rs * Elem<CT>::to_f32(gn[lane]);
           x1 *= rs * Elem<CT>::to_f32(gn[lane + half]);
-          double sn, cs;
-          sincos((double)(pos_first + row) * inv_freq[lane], &sn, &cs);
-          const float c = (float)cs, sf = (float)sn;
+          const float2 cs = rope_tab[(size_t)(pos_first + row) * half + lane];
+          const float c = cs.x, sf = cs.y;
           const float y0 = x0 * c - x1 * sf, y1 = x1 * c + x0 * sf;
           if (is_q) {
             q_s[v][lane] = y0 * scale; q_s[v][lane + half] = y1 * scale;

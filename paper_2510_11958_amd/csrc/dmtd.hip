@@ -31,6 +31,7 @@ constexpr int kMaxRows = 16;         // rows per sequence one pass through the l
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
 constexpr int kMfmaRows = 16;        // activation rows per MFMA weight-streaming pass
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
+constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter runs put 8 waves on a tile (measured 8.3 us instead of 9.3 us at 4B shapes)
 
 thread_local std::string g_create_error;
 
@@ -44,7 +45,7 @@ struct LayerSw {  // the layer's matrices in MFMA operand order (workspace; bf16
 struct Ws {   // device workspace carve-up (byte offsets)
   size_t kv, kv_layer_stride, kv_v_off;
   size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, amax;
-  size_t tokens, emitted, forced, state, inv_freq;
+  size_t tokens, emitted, forced, state, inv_freq, rope_tab;
   size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
   size_t total;
 };
@@ -145,6 +146,7 @@ Ws layout(const dmtd_config& c) {
   w.forced = take((size_t)kMaxTau * B * 4);
   w.state = take(256);
   w.inv_freq = take((hd / 2) * 8);
+  w.rope_tab = take(S * (hd / 2) * 8);                 // (cos, sin) per position and frequency
   if (c.dtype == DMTD_DTYPE_BF16) {
     const size_t parts = (d + 15) / 16;
     w.xb = take(rows * d * 2);
@@ -238,15 +240,15 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
 // ---------------------------------------------------- packed path: MFMA weight streaming
 
 // nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4}) that lets a wave
-// hold its k-range in one round of kMfmaPF k-steps, else the largest with several rounds.
+// hold its k-range in one round of PF k-steps, else the largest with several rounds.
 // Rows beyond 16 go in further launches (each streams the matrix again).
-template <int EPI, bool NORM>
+template <int EPI, bool NORM, int PF = kMfmaPF>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
   constexpr int MATS = EPI == EPI_SWIGLU ? 2 : 1;
   const int nw_max = EPI == EPI_SWIGLU ? 4 : 8;
   int nw = 2;
-  while (nw < nw_max && (KS + nw - 1) / nw > kMfmaPF) nw *= 2;
+  while (nw < nw_max && (KS + nw - 1) / nw > PF) nw *= 2;
   const dim3 grid((a.N + 15) / 16);
   for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
     MfmaArgs g = a;
@@ -262,8 +264,8 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
     const bool blds = lds <= 60 * 1024;
 #define DMTD_LAUNCH_MFMA(NWT_)                                                                                              \
     do {                                                                                                                    \
-      if (blds) hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF, NWT_, true>), grid, dim3(64 * NWT_), lds, c->stream, g); \
-      else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, kMfmaPF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);       \
+      if (blds) hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>), grid, dim3(64 * NWT_), lds, c->stream, g); \
+      else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);       \
     } while (0)
     if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
     else if (nw == 4) DMTD_LAUNCH_MFMA(4 * MATS);
@@ -302,7 +304,7 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel,
   float* pml = (float*)(c->ws + c->o.part_ml);
   const DevState* st = dev_state(c);
   hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
-                     w.q_norm, w.k_norm, (const double*)(c->ws + c->o.inv_freq), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
+                     w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
                      cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
@@ -395,7 +397,7 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
     // a2: RMSNorm + fused QKV projection
     a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
-    if ((e = launch_mfma<EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
+    if ((e = launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows)) != hipSuccess) return e;
     // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge (output packed for the O projection)
     if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
     // a5: O projection + residual; emits the MLP norm's input
@@ -592,7 +594,7 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     switch (kind) {
       case DMTD_K_QKV:
         a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = 1; a.y = qkv; a.ldy = nqkv;
-        return launch_mfma<EPI_STORE, true>(c, a, rows);
+        return launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows);
       case DMTD_K_OPROJ:
         a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
         a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp;
@@ -699,6 +701,11 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
     std::vector<double> inv(hd / 2);
     for (size_t i = 0; i < hd / 2; ++i) inv[i] = std::pow((double)cfg->rope_theta, -2.0 * (double)i / (double)hd);
     hipError_t e = hipMemcpyAsync(c->ws + lay.inv_freq, inv.data(), inv.size() * 8, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL(rope_table_kernel, dim3(1024), dim3(256), 0, c->stream, (const double*)(c->ws + lay.inv_freq),
+                         (float2*)(c->ws + lay.rope_tab), cfg->max_seq_len, (int)(hd / 2));
+      e = hipGetLastError();
+    }
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)AMAX_CELLS * cfg->max_batch * 8, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, 256, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
