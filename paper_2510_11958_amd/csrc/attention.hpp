@@ -122,6 +122,62 @@ __global__ void rope_table_kernel(const double* __restrict__ inv_freq, float2* _
   }
 }
 
+// Per-head RMSNorm + RoPE (pair (i, i + HD/2), cos/sin from the table) of a block's QV query vectors
+// (rows row0 .. of the launch, GQ heads each, scaled by 1/sqrt(HD)) into q_s and, if the block's key
+// range holds new positions, of the launch's first n_new keys and values into knew_s / vnew_s, rounded
+// to the cache's type; the writer block also stores them to the cache.  Called by all 4 waves of a block.
+template <typename CT, int HD>
+__device__ __forceinline__ void attn_prepare_rows(
+    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
+    const float2* __restrict__ rope_tab, CT* __restrict__ kc, CT* __restrict__ vc, int b, int g, int nh, int nkv, int s_max,
+    float eps, int r_total, int row0, int QV, int n_new, bool holds_new, bool writer, int pos_first, int key_begin, int key_end,
+    float (*q_s)[HD], float (*knew_s)[HD], float (*vnew_s)[HD], int lane, int wave) {
+  constexpr int half = HD / 2;
+  const int GQ = nh / nkv;
+  const float scale = rsqrtf((float)HD);
+  const bool act = lane < half;
+  const int n_vec = QV + (holds_new ? 2 * n_new : 0);         // queries, new keys, new values
+  for (int v = wave; v < n_vec; v += 4) {
+    if (v < QV + n_new) {
+      const bool is_q = v < QV;
+      const int row = is_q ? row0 + v / GQ : v - QV;          // row of the launch
+      const int hcol = is_q ? g * GQ + v % GQ : nh + g;
+      const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD;
+      float x0 = act ? src[lane] : 0.f, x1 = act ? src[lane + half] : 0.f;
+      const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)HD + eps);
+      if (act) {
+        const CT* gn = (const CT*)(is_q ? q_gain : k_gain);
+        x0 *= rs * Elem<CT>::to_f32(gn[lane]);
+        x1 *= rs * Elem<CT>::to_f32(gn[lane + half]);
+        const float2 cs = rope_tab[(size_t)(pos_first + row) * half + lane];
+        const float c = cs.x, sf = cs.y;
+        const float y0 = x0 * c - x1 * sf, y1 = x1 * c + x0 * sf;
+        if (is_q) {
+          q_s[v][lane] = y0 * scale; q_s[v][lane + half] = y1 * scale;
+        } else {
+          const CT c0 = Elem<CT>::from_f32(y0), c1 = Elem<CT>::from_f32(y1);
+          knew_s[row][lane] = Elem<CT>::to_f32(c0); knew_s[row][lane + half] = Elem<CT>::to_f32(c1);
+          const int key = pos_first + row;
+          if (writer && key >= key_begin && key < key_end) {
+            CT* dst = kc + (((size_t)b * nkv + g) * s_max + key) * HD;
+            dst[lane] = c0; dst[lane + half] = c1;
+          }
+        }
+      }
+    } else {
+      const int row = v - QV - n_new, key = pos_first + row;
+      const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)(nh + nkv + g) * HD;
+      CT* dst = vc + (((size_t)b * nkv + g) * s_max + key) * HD;
+      const bool wr = writer && key >= key_begin && key < key_end;
+      for (int k = lane; k < HD; k += 64) {
+        const CT cv = Elem<CT>::from_f32(src[k]);
+        vnew_s[row][k] = Elem<CT>::to_f32(cv);
+        if (wr) dst[k] = cv;
+      }
+    }
+  }
+}
+
 template <typename CT, int HD, int QVT>
 __global__ void __launch_bounds__(256) attn_split_kernel(
     const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
@@ -180,51 +236,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
   const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
   const float scale = rsqrtf((float)HD);
 
-  // ---- per-head RMSNorm + RoPE (pair (i, i + HD/2)) of this block's queries and, where needed, of the new keys
-  {
-    constexpr int half = HD / 2;
-    const bool act = lane < half;
-    const int n_vec = QV + (holds_new ? 2 * n_new : 0);         // queries, new keys, new values
-    for (int v = wave; v < n_vec; v += 4) {
-      if (v < QV + n_new) {
-        const bool is_q = v < QV;
-        const int row = is_q ? rg * rpb + v / GQ : v - QV;      // row of the launch
-        const int hcol = is_q ? g * GQ + v % GQ : nh + g;
-        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD;
-        float x0 = act ? src[lane] : 0.f, x1 = act ? src[lane + half] : 0.f;
-        const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)HD + eps);
-        if (act) {
-          const CT* gn = (const CT*)(is_q ? q_gain : k_gain);
-          x0 *= rs * Elem<CT>::to_f32(gn[lane]);
-          x1 *= rs * Elem<CT>::to_f32(gn[lane + half]);
-          const float2 cs = rope_tab[(size_t)(pos_first + row) * half + lane];
-          const float c = cs.x, sf = cs.y;
-          const float y0 = x0 * c - x1 * sf, y1 = x1 * c + x0 * sf;
-          if (is_q) {
-            q_s[v][lane] = y0 * scale; q_s[v][lane + half] = y1 * scale;
-          } else {
-            const CT c0 = Elem<CT>::from_f32(y0), c1 = Elem<CT>::from_f32(y1);
-            knew_s[row][lane] = Elem<CT>::to_f32(c0); knew_s[row][lane + half] = Elem<CT>::to_f32(c1);
-            const int key = pos_first + row;
-            if (writer && key >= key_begin && key < key_end) {
-              CT* dst = kc + (((size_t)b * nkv + g) * s_max + key) * HD;
-              dst[lane] = c0; dst[lane + half] = c1;
-            }
-          }
-        }
-      } else {
-        const int row = v - QV - n_new, key = pos_first + row;
-        const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)(nh + nkv + g) * HD;
-        CT* dst = vc + (((size_t)b * nkv + g) * s_max + key) * HD;
-        const bool wr = writer && key >= key_begin && key < key_end;
-        for (int k = lane; k < HD; k += 64) {
-          const CT cv = Elem<CT>::from_f32(src[k]);
-          vnew_s[row][k] = Elem<CT>::to_f32(cv);
-          if (wr) dst[k] = cv;
-        }
-      }
-    }
-  }
+  attn_prepare_rows<CT, HD>(qkv, ldq, q_gain, k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total, rg * rpb, QV, n_new, holds_new,
+                            writer, pos_first, key_begin, key_end, q_s, knew_s, vnew_s, lane, wave);
   __syncthreads();
 
   float q[QVT][8];
@@ -292,9 +305,9 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
 // Merge the ranges' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
 // f_s = exp(m_s - max_s m_s), ranges taken in order.  One block (128 threads) per (row, query head,
 // sequence); every load is issued before the first one is needed.
-template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection)
+template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection: high parts to out, low parts to out_lo)
 __global__ void __launch_bounds__(128) attn_merge_kernel(
-    const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, int ldo,
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, OT* __restrict__ out_lo, int ldo,
     int nh, int nkv, int kps, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
   constexpr int PRE = 32;                 // ranges whose partials a thread fetches before anything is waited for
   const int i = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
@@ -347,7 +360,11 @@ __global__ void __launch_bounds__(128) attn_merge_kernel(
       const float v = part_o[((slot0 + s2) * qv_stride + qv) * HD + tid];
       o += (f == 0.f) ? 0.f : f * v;
     }
-    out[(size_t)(b * r_total + i) * ldo + (size_t)head * HD + tid] = Elem<OT>::from_f32(o * inv_l_s);
+    const size_t at = (size_t)(b * r_total + i) * ldo + (size_t)head * HD + tid;
+    const float res = o * inv_l_s;
+    const OT hi = Elem<OT>::from_f32(res);
+    out[at] = hi;
+    if (out_lo) out_lo[at] = Elem<OT>::from_f32(res - Elem<OT>::to_f32(hi));
   }
 }
 

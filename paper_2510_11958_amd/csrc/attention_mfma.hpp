@@ -1,0 +1,221 @@
+// Split-K decode attention on the matrix cores, for a bf16 KV cache and up to 16 query vectors per
+// KV head (rows of a sequence x query heads that share the KV head), all served by ONE pass over
+// K and V.  With several rows per sequence (the refill rows of a full step) the vector kernel runs
+// out of registers and of vector ALU throughput; here the 16 query vectors are the 16 columns of
+// an MFMA tile, so a block reads each key and value once whatever the number of rows.
+//
+// Same launch shape, prologue (QK-norm, RoPE, append of the new rows) and partial-result format
+// as attn_split_kernel; the same merge kernel follows.  A block = (key range, row group, KV head,
+// sequence) with 16 / (query heads per KV head) rows per group (launches with more rows, e.g. prefill
+// chunks, read K and V once per group); its 4 waves take interleaved groups of 16 keys.  Per group of 16 keys, in one wave:
+//   scores   S^T[key, q] = sum_d K[key, d] Q[q, d]      v_mfma_f32_16x16x32_bf16, K rows as the A
+//            operand (a lane loads 8 consecutive d of one key: 16 bytes straight from the cache), the
+//            queries as B, each split into a bf16 high and low part (two MFMAs) so that they keep
+//            16 mantissa bits; the result leaves lane (q = lane % 16, kq = lane / 16) with the
+//            scores of keys 4 kq .. 4 kq + 3 for query q;
+//   softmax  running maximum and sum per query in those lanes (maximum across the 4 kq lanes by
+//            two shuffles);
+//   output   O[q, d] += sum_key P[q, key] V[key, d]     v_mfma_f32_16x16x4_f32 (contraction over 4 keys,
+//            one fp32 value per lane and operand, so no operand has to be transposed): for m = 0..3 the A
+//            operand is the lane's own p of key 4 kq + m, the B operand the lane's own V[4 kq + m][8 sl + e]
+//            (sl = lane % 16; the lane loaded those 8 consecutive d with one 16-byte load), one MFMA
+//            per e; accumulator e of lane (sl, kq) holds O[4 kq + j][8 sl + e], j = 0..3.
+// Nothing moves between lanes except the maxima and the per-query rescale factors.
+#pragma once
+#include "attention.hpp"
+#include "gemv_mfma.hpp"
+
+namespace dmtd {
+
+template <int HD>
+__global__ void __launch_bounds__(256) attn_split_mfma_kernel(
+    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
+    const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+    float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
+    int kps /* keys per range, a multiple of 64 */, int n_splits, int qv_stride,
+    const DevState* st, int sel, int offset, int r_total, int do_append) {
+  constexpr int QVT = 16;
+  constexpr int KSTEPS = HD / 32;      // MFMA steps over d for the scores
+  constexpr int DPL = HD / 16;         // output dims per lane (8 or 4)
+  constexpr int NEW_MAX = 16;
+  typedef unsigned int vraw_t __attribute__((ext_vector_type(DPL / 2)));   // DPL bf16 values
+
+  const int g = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int GQ = nh / nkv;
+  const int rpb = QVT / GQ;                                    // rows per block
+  const int n_rg = (r_total + rpb - 1) / rpb;
+  const int split = blockIdx.x / n_rg, rg = blockIdx.x % n_rg;
+  const int r = min(rpb, r_total - rg * rpb), QV = r * GQ;
+  const int key_begin = split * kps;
+  const int sl = lane & 15, kq = lane >> 4;
+
+  __shared__ float q_s[QVT][HD];
+  __shared__ float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
+  __shared__ float wacc[4][QVT][HD];
+  __shared__ float wm[4][QVT], wl[4][QVT];
+
+  const bf16_t* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD;
+  const bf16_t* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD;
+  // K: lane (key = sl, d group kq) per step t: K[key][32 t + 8 kq ..]; V: lane (dims DPL sl .., keys 4 kq + m)
+  u32x4 kr[KSTEPS];
+  vraw_t vr[4];
+  auto load_kv = [&](int base, int limit) {
+    const int kkey = base + sl;
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t)
+      kr[t] = kkey < limit ? __builtin_nontemporal_load((const u32x4*)(kbase + (size_t)kkey * HD + 32 * t + 8 * kq)) : u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const int vkey = base + 4 * kq + m;
+      vraw_t z;
+#pragma unroll
+      for (int e = 0; e < DPL / 2; ++e) z[e] = 0u;
+      vr[m] = vkey < limit ? __builtin_nontemporal_load((const vraw_t*)(vbase + (size_t)vkey * HD + DPL * sl)) : z;
+    }
+  };
+  const int range_limit = min(s_max, key_begin + kps);
+  load_kv(key_begin + 16 * wave, range_limit);
+
+  const int pos_first = row_base(st, sel, offset);
+  const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
+  const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
+  if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
+  const int key_end = min(ctx, key_begin + kps);
+  const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
+  const bool holds_new = key_end > pos_first;
+  const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
+
+  attn_prepare_rows<bf16_t, HD>(qkv, ldq, q_gain, k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total, rg * rpb, QV, n_new, holds_new,
+                                writer, pos_first, key_begin, key_end, q_s, knew_s, vnew_s, lane, wave);
+  __syncthreads();
+
+  // queries as B operands: lane (q = sl, d group kq), high and low bf16 parts
+  bf16x8_t qhi[KSTEPS], qlo[KSTEPS];
+#pragma unroll
+  for (int t = 0; t < KSTEPS; ++t) {
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float x0 = sl < QV ? q_s[sl][32 * t + 8 * kq + 2 * e] : 0.f, x1 = sl < QV ? q_s[sl][32 * t + 8 * kq + 2 * e + 1] : 0.f;
+      const uint32_t h = pack_bf16x2(x0, x1);
+      hi[e] = h;
+      lo[e] = pack_bf16x2(x0 - __uint_as_float(h << 16), x1 - __uint_as_float(h & 0xFFFF0000u));
+    }
+    qhi[t] = __builtin_bit_cast(bf16x8_t, u32x4{hi[0], hi[1], hi[2], hi[3]});
+    qlo[t] = __builtin_bit_cast(bf16x8_t, u32x4{lo[0], lo[1], lo[2], lo[3]});
+  }
+  const int my_row_pos = pos0 + sl / GQ;                   // query sl belongs to row sl / GQ: it sees keys <= this position
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 acc[DPL];
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int it0 = key_begin; it0 < key_end; it0 += 64) {
+    const int base = it0 + 16 * wave;                           // this wave's 16 keys
+    u32x4 ka[KSTEPS];
+    float vf[4][DPL];
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) ka[t] = kr[t];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int e = 0; e < DPL / 2; ++e) {
+        vf[m][2 * e] = __uint_as_float(vr[m][e] << 16);
+        vf[m][2 * e + 1] = __uint_as_float(vr[m][e] & 0xFFFF0000u);
+      }
+    if (it0 + 64 < key_end) load_kv(base + 64, key_end);        // the next iteration's keys fly during this one
+    if (holds_new) {
+      // new positions: key and value come from LDS (the cache slot is written by this launch, maybe not yet)
+      const int ik = base + sl - pos_first;
+      if (ik >= 0 && ik < n_new) {
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) {
+          const float* src = &knew_s[ik][32 * t + 8 * kq];
+          ka[t] = u32x4{pack_bf16x2(src[0], src[1]), pack_bf16x2(src[2], src[3]), pack_bf16x2(src[4], src[5]), pack_bf16x2(src[6], src[7])};
+        }
+      }
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const int iv = base + 4 * kq + m - pos_first;
+        if (iv >= 0 && iv < n_new) {
+#pragma unroll
+          for (int e = 0; e < DPL; ++e) vf[m][e] = vnew_s[iv][DPL * sl + e];
+        }
+      }
+    }
+    // scores of keys base + 4 kq + j for query sl
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) {
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t]), qhi[t], s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[t]), qlo[t], s, 0, 0, 0);
+    }
+    float sc[4] = {s.x, s.y, s.z, s.w};
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = base + 4 * kq + j;
+      if (key >= key_end || key > my_row_pos || sl >= QV) sc[j] = -INFINITY;
+      mx = fmaxf(mx, sc[j]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    float p[4] = {0.f, 0.f, 0.f, 0.f};
+    float resc = 1.f;
+    if (m_new != -INFINITY) {
+      resc = __expf(m_run - m_new);                             // exp(-inf) = 0 on the first visible key
+      float psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        p[j] = sc[j] == -INFINITY ? 0.f : __expf(sc[j] - m_new);
+        psum += p[j];
+      }
+      l_run = l_run * resc + psum;
+      m_run = m_new;
+    }
+    // rescale the output rows this lane holds (queries 4 kq + j) by their queries' factors
+    float rj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rj[j] = __shfl(resc, 4 * kq + j, 64);
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) { acc[e].x *= rj[0]; acc[e].y *= rj[1]; acc[e].z *= rj[2]; acc[e].w *= rj[3]; }
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[m], vf[m][e], acc[e], 0, 0, 0);
+  }
+
+  // per-wave totals: l summed over the 4 kq lanes of a query
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (kq == 0 && sl < QV) { wm[wave][sl] = m_run; wl[wave][sl] = l_run; }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int qv = 4 * kq + j;
+    if (qv < QV) {
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) wacc[wave][qv][DPL * sl + e] = acc[e][j];
+    }
+  }
+  __syncthreads();
+  const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
+  float* my_o = part_o + slot * HD;
+  float* my_ml = part_ml + slot * 2;
+  for (int e = tid; e < QV * HD; e += 256) {
+    const int qv = e / HD, d = e % HD;
+    const float mm = fmaxf(fmaxf(wm[0][qv], wm[1][qv]), fmaxf(wm[2][qv], wm[3][qv]));
+    float o = 0.f, ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
+      o += f * wacc[w][qv][d];
+      ll += f * wl[w][qv];
+    }
+    my_o[qv * HD + d] = o;
+    if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
+  }
+}
+
+}  // namespace dmtd

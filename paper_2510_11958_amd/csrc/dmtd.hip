@@ -11,11 +11,13 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 #include <map>
 #include <string>
 #include <tuple>
+#include <type_traits>
 #include <vector>
 
 #include "kernels.hpp"
@@ -31,6 +33,7 @@ constexpr int kMaxRows = 16;         // rows per sequence one pass through the l
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
 constexpr int kMfmaRows = 16;        // activation rows per MFMA weight-streaming pass
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
+constexpr int kMfmaPFGateUp = 8;     // the same for gate/up: with the two activation planes 10 steps no longer fit 128 registers (two blocks per CU)
 constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter runs put 8 waves on a tile (measured 8.3 us instead of 9.3 us at 4B shapes)
 
 thread_local std::string g_create_error;
@@ -54,7 +57,8 @@ struct Ws {   // device workspace carve-up (byte offsets)
 // the norm that reads the rows next) and ssp the partial sums of h^2 (n_parts of them per row).
 struct Rows {
   float* h;
-  bf16_t* xb;
+  bf16_t* xb;      // high parts
+  bf16_t* xb_lo;   // low parts
   float* ssp;
   int n_parts;
 };
@@ -149,8 +153,8 @@ Ws layout(const dmtd_config& c) {
   w.rope_tab = take(S * (hd / 2) * 8);                 // (cos, sin) per position and frequency
   if (c.dtype == DMTD_DTYPE_BF16) {
     const size_t parts = (d + 15) / 16;
-    w.xb = take(rows * d * 2);
-    w.xb_late = take(B * d * 2);
+    w.xb = take(rows * d * 2 * 2);                     // high and low planes
+    w.xb_late = take(B * d * 2 * 2);
     w.ssp = take(parts * rows * 4);
     w.ssp_late = take(parts * rows * 4);
     w.wsw = take((swizzled_layer_elems(c) * c.n_layers + swizzled_elems(c.vocab, d)) * 2);
@@ -239,37 +243,49 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
 
 // ---------------------------------------------------- packed path: MFMA weight streaming
 
-// nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4}) that lets a wave
+// nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4, 5}) that lets a wave
 // hold its k-range in one round of PF k-steps, else the largest with several rounds.
 // Rows beyond 16 go in further launches (each streams the matrix again).
 template <int EPI, bool NORM, int PF = kMfmaPF>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
   constexpr int MATS = EPI == EPI_SWIGLU ? 2 : 1;
-  const int nw_max = EPI == EPI_SWIGLU ? 4 : 8;
+  const int nw_max = EPI == EPI_SWIGLU ? 5 : 8;
   int nw = 2;
-  while (nw < nw_max && (KS + nw - 1) / nw > PF) nw *= 2;
+  while (nw < nw_max && (KS + nw - 1) / nw > PF) nw = (EPI == EPI_SWIGLU && nw == 4) ? 5 : nw * 2;
   const dim3 grid((a.N + 15) / 16);
   for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
     MfmaArgs g = a;
     g.M = rows - m0 < kMfmaRows ? rows - m0 : kMfmaRows;
     g.xb = a.xb + (size_t)m0 * a.ldxb;
+    g.xb_lo = a.xb_lo + (size_t)m0 * a.ldxb;
     if (a.ssp) g.ssp = a.ssp + m0;
     if (a.y) g.y = a.y + (size_t)m0 * a.ldy;
-    if (a.yb) g.yb = a.yb + (size_t)m0 * a.ldyb;
+    if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
     if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
     if (a.amax) g.amax = a.amax + m0;
-    // B operands through LDS when the packed rows fit comfortably (frees registers: more waves per CU)
-    const size_t lds = (size_t)g.M * (a.K + 8) * 2;
-    const bool blds = lds <= 60 * 1024;
+    // B operands (both planes) through LDS when the packed rows fit: comfortably (two blocks per CU) in
+    // general, up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway
+    const size_t lds = (size_t)2 * g.M * a.K * 2;
+    const bool blds = a.ldxb == a.K && lds <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
 #define DMTD_LAUNCH_MFMA(NWT_)                                                                                              \
     do {                                                                                                                    \
-      if (blds) hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>), grid, dim3(64 * NWT_), lds, c->stream, g); \
-      else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);       \
+      if (blds) {                                                                                                           \
+        auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>;                                                            \
+        static bool big_lds = false;                                                                                        \
+        if (lds > 48 * 1024 && !big_lds) {                                                                                  \
+          hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);   \
+          if (ae != hipSuccess) return ae;                                                                                  \
+          big_lds = true;                                                                                                   \
+        }                                                                                                                   \
+        hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g);                                                 \
+      } else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);    \
     } while (0)
     if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
     else if (nw == 4) DMTD_LAUNCH_MFMA(4 * MATS);
-    else {
+    else if (nw == 5) {
+      if constexpr (EPI == EPI_SWIGLU) DMTD_LAUNCH_MFMA(10);
+    } else {
       if constexpr (EPI != EPI_SWIGLU) DMTD_LAUNCH_MFMA(8);
     }
 #undef DMTD_LAUNCH_MFMA
@@ -283,7 +299,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
 // The ranges follow from the context bucket (c->att_bucket, a multiple of 512 that covers the context), so a
 // captured step stays valid until the sequence grows into the next bucket.
 template <typename CT, typename OT, int HD, int QVT>
-void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r, int append) {
+void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
   const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = QVT / gq, n_rg = (r + rpb - 1) / rpb;
@@ -306,27 +322,61 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel,
   hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
                      cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
-  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, qd,
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, attn_lo, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
 }
 
-// share_kv: all rows of a sequence go through one block so that K and V are read once
-// (long contexts); otherwise rows are spread over blocks (short contexts, K/V re-reads hit in L2).
+// The matrix-core kernel (bf16 caches): one pass over K and V serves up to 16 query vectors per KV head.
+template <typename OT, int HD>
+void launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append) {
+  const dmtd_config& cf = c->cfg;
+  const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
+  const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = 16 / gq, n_rg = (r + rpb - 1) / rpb;
+  constexpr int KPI = 64;
+  bf16_t* kc = (bf16_t*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  bf16_t* vc = (bf16_t*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  const LayerW& w = c->layers[l];
+  const int bucket = c->att_bucket;
+  long per_split_blocks = (long)cf.n_kv_heads * B * n_rg;
+  int want_splits = (int)((4L * c->num_cus + per_split_blocks - 1) / per_split_blocks);
+  if (want_splits > ATT_MAX_SPLITS) want_splits = ATT_MAX_SPLITS;
+  if (want_splits < 1) want_splits = 1;
+  int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
+  const int ns = (bucket + kps - 1) / kps;
+  float* po = (float*)(c->ws + c->o.part_o);
+  float* pml = (float*)(c->ws + c->o.part_ml);
+  const DevState* st = dev_state(c);
+  hipLaunchKernelGGL((attn_split_mfma_kernel<HD>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
+                     w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
+                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, attn_lo, qd,
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
+}
+
+// Kernel choice.  bf16 caches: the matrix-core kernel (measured faster than the vector kernel even for
+// one row and 4 query heads per KV head: 11.7 vs 13.2 us at 1k context, 99 vs 119 us at 8 x 16k).
+// fp32 caches: the vector kernel; share_kv: all rows of a sequence go through one block so that K and V
+// are read once (long contexts), else rows are spread over blocks (K/V re-reads hit in L2).
 template <typename CT, typename OT>
-hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, int sel, int offset, int r, int append = 1) {
+hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append = 1) {
   const dmtd_config& cf = c->cfg;
   const int gq = cf.n_q_heads / cf.n_kv_heads;
   if (r > kMaxRows) return hipErrorInvalidValue;
+  if constexpr (std::is_same<CT, bf16_t>::value) {
+    if (cf.head_dim == 128) launch_attention_mfma_t<OT, 128>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    else launch_attention_mfma_t<OT, 64>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    return hipGetLastError();
+  }
   const int want = c->share_kv ? r * gq : gq;
   const int qvt = want <= 4 ? 4 : (want <= 8 ? 8 : 16);
   if (cf.head_dim == 128) {
-    if (qvt == 4) launch_attention_t<CT, OT, 128, 4>(c, l, qkv, attn, sel, offset, r, append);
-    else if (qvt == 8) launch_attention_t<CT, OT, 128, 8>(c, l, qkv, attn, sel, offset, r, append);
-    else launch_attention_t<CT, OT, 128, 16>(c, l, qkv, attn, sel, offset, r, append);
+    if (qvt == 4) launch_attention_t<CT, OT, 128, 4>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    else if (qvt == 8) launch_attention_t<CT, OT, 128, 8>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    else launch_attention_t<CT, OT, 128, 16>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
   } else {
-    if (qvt == 4) launch_attention_t<CT, OT, 64, 4>(c, l, qkv, attn, sel, offset, r, append);
-    else if (qvt == 8) launch_attention_t<CT, OT, 64, 8>(c, l, qkv, attn, sel, offset, r, append);
-    else launch_attention_t<CT, OT, 64, 16>(c, l, qkv, attn, sel, offset, r, append);
+    if (qvt == 4) launch_attention_t<CT, OT, 64, 4>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    else if (qvt == 8) launch_attention_t<CT, OT, 64, 8>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    else launch_attention_t<CT, OT, 64, 16>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
   }
   return hipGetLastError();
 }
@@ -340,7 +390,7 @@ hipError_t embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int next
   if (c->packed) {
     hipLaunchKernelGGL(embed_pack_kernel, dim3(rows), dim3(256), 0, c->stream, (const bf16_t*)c->embed, dev_tokens(c),
                        cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h, (const bf16_t*)norm_gain_for_layer(c, next_layer),
-                       R.xb, R.ssp);
+                       R.xb, R.xb_lo, R.ssp);
     R.n_parts = 1;
   } else {
     hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, c->stream, (const float*)c->embed, dev_tokens(c),
@@ -356,7 +406,7 @@ hipError_t add_embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int 
   if (c->packed) {
     hipLaunchKernelGGL(add_embed_pack_kernel, dim3(rows), dim3(256), 0, c->stream, R.h, (const bf16_t*)c->embed, dev_tokens(c),
                        cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, (const bf16_t*)norm_gain_for_layer(c, next_layer),
-                       R.xb, R.ssp);
+                       R.xb, R.xb_lo, R.ssp);
     R.n_parts = 1;
   } else {
     hipLaunchKernelGGL(add_embed_rows_kernel<float>, dim3(rows), dim3(256), 0, c->stream, R.h, (const float*)c->embed,
@@ -371,7 +421,7 @@ hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int ad
   if (c->packed) {
     hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden, add_embed,
                        (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset,
-                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.ssp);
+                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp);
     dst.n_parts = 1;
   } else {
     hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden,
@@ -390,30 +440,33 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   hipError_t e;
   if (c->packed) {
     const LayerSw& s = c->sw[l];
-    bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);
-    bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);
+    const size_t rows_cap = (size_t)cf.max_batch * kMaxRows;
+    bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);      // attention output, high parts; low parts behind them
+    bf16_t* ab_lo = ab + rows_cap * qd;
+    bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);       // SwiGLU output, likewise
+    bf16_t* ub_lo = ub + rows_cap * ff;
     const int tiles_d = (d + 15) / 16;
     MfmaArgs a{};
     // a2: RMSNorm + fused QKV projection
-    a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
+    a.W = s.qkv; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
     if ((e = launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows)) != hipSuccess) return e;
     // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge (output packed for the O projection)
-    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, sel, offset, r)) != hipSuccess) return e;
+    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, ab_lo, sel, offset, r)) != hipSuccess) return e;
     // a5: O projection + residual; emits the MLP norm's input
     a = MfmaArgs{};
-    a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+    a.W = s.o; a.xb = ab; a.xb_lo = ab_lo; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
     a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
     if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
     R.n_parts = tiles_d;
     // a6: RMSNorm + gate/up + SwiGLU
     a = MfmaArgs{};
-    a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts;
-    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.yb = ub; a.ldyb = ff;
+    a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts;
+    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.yb = ub; a.yb_lo = ub_lo; a.ldyb = ff;
     if ((e = launch_mfma<EPI_SWIGLU, true>(c, a, rows)) != hipSuccess) return e;
     // a7: down projection + residual; emits the next layer's (or the final) norm input
     a = MfmaArgs{};
-    a.W = s.down; a.xb = ub; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+    a.W = s.down; a.xb = ub; a.xb_lo = ub_lo; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
     a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
     if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
     R.n_parts = tiles_d;
@@ -427,7 +480,7 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
   if ((e = gemv_rows<float, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
   // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge
-  if ((e = launch_attention<float, float>(c, l, qkv, attn, sel, offset, r)) != hipSuccess) return e;
+  if ((e = launch_attention<float, float>(c, l, qkv, attn, (float*)nullptr, sel, offset, r)) != hipSuccess) return e;
   // a5: O projection + residual
   a = GemvArgs{};
   a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
@@ -450,7 +503,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
   hipError_t e;
   if (c->packed) {
     MfmaArgs a{};
-    a.W = c->lm_head_sw; a.xb = R.xb; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
+    a.W = c->lm_head_sw; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
     a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
     a.amax = amax; a.amax_ld = cf.max_batch;
     e = launch_mfma<EPI_LOGITS, true>(c, a, n_rows);
@@ -469,10 +522,12 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
 }
 
 Rows front_rows(dmtd_ctx* c) {
-  return Rows{(float*)(c->ws + c->o.h), (bf16_t*)(c->ws + c->o.xb), (float*)(c->ws + c->o.ssp), 1};
+  bf16_t* xb = (bf16_t*)(c->ws + c->o.xb);
+  return Rows{(float*)(c->ws + c->o.h), xb, xb + (size_t)c->cfg.max_batch * kMaxRows * c->cfg.hidden, (float*)(c->ws + c->o.ssp), 1};
 }
 Rows late_rows(dmtd_ctx* c) {
-  return Rows{(float*)(c->ws + c->o.h_late), (bf16_t*)(c->ws + c->o.xb_late), (float*)(c->ws + c->o.ssp_late), 1};
+  bf16_t* xb = (bf16_t*)(c->ws + c->o.xb_late);
+  return Rows{(float*)(c->ws + c->o.h_late), xb, xb + (size_t)c->cfg.max_batch * c->cfg.hidden, (float*)(c->ws + c->o.ssp_late), 1};
 }
 
 // One decode step (Sec. 2.2).  Full: embed the pending rows and the newest row, run the front
@@ -578,8 +633,8 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     const int r = rows <= last + 1 ? rows : 1;
     // the cache append is switched off: the launch scores the rows' new keys from the scratch q/k/v, writes nothing
     choose_attention(c, last + 1);
-    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r, 0);
-    return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (int)POS_EXPLICIT, last - r + 1, r, 0);
+    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (bf16_t*)(c->ws + c->o.attn) + (size_t)cf.max_batch * kMaxRows * cf.n_q_heads * cf.head_dim, (int)POS_EXPLICIT, last - r + 1, r, 0);
+    return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (float*)nullptr, (int)POS_EXPLICIT, last - r + 1, r, 0);
   }
   if (kind == DMTD_K_LMHEAD) {
     R.n_parts = 1;
@@ -587,24 +642,27 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
   }
   if (c->packed) {
     const LayerSw& s = c->sw[l];
+    const size_t rows_cap = (size_t)cf.max_batch * kMaxRows;
     bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);
+    bf16_t* ab_lo = ab + rows_cap * qd;
     bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);
+    bf16_t* ub_lo = ub + rows_cap * ff;
     MfmaArgs a{};
     a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps;
     switch (kind) {
       case DMTD_K_QKV:
-        a.W = s.qkv; a.xb = R.xb; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = 1; a.y = qkv; a.ldy = nqkv;
+        a.W = s.qkv; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = 1; a.y = qkv; a.ldy = nqkv;
         return launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows);
       case DMTD_K_OPROJ:
-        a.W = s.o; a.xb = ab; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+        a.W = s.o; a.xb = ab; a.xb_lo = ab_lo; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
         a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp;
         return launch_mfma<EPI_RESID, false>(c, a, rows);
       case DMTD_K_GATEUP:
-        a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = (d + 15) / 16;
-        a.yb = ub; a.ldyb = ff;
+        a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = (d + 15) / 16;
+        a.yb = ub; a.yb_lo = ub_lo; a.ldyb = ff;
         return launch_mfma<EPI_SWIGLU, true>(c, a, rows);
       default:
-        a.W = s.down; a.xb = ub; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.ldyb = d;
+        a.W = s.down; a.xb = ub; a.xb_lo = ub_lo; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
         a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp;
         return launch_mfma<EPI_RESID, false>(c, a, rows);
     }

@@ -9,7 +9,10 @@
 // read exactly once, and no data passes through LDS or is converted on the way.
 //
 // The activation rows are the B operand (column = lane % 16, zero beyond M); they arrive
-// already packed in bf16, written by the kernel that produced them.  RMSNorm is folded in
+// already packed, written by the kernel that produced them, as TWO bf16 planes: hi = bf16(x)
+// and lo = bf16(x - hi).  Each k-step takes two matrix-core passes (W * hi + W * lo), which the
+// weight stream hides, so the activations keep 16 mantissa bits and the only bf16 roundings left
+// on the path are those of the stored model (weights, KV cache).  RMSNorm is folded in
 // exactly: the producer stores bf16(x * gain) and per-tile partial sums of x^2, and the
 // epilogue here multiplies column m by rsqrt(mean(x_m^2) + eps).  No cross-lane reduction
 // is needed: the matrix core sums over k, and a lane ends up holding 4 rows of one column.
@@ -35,6 +38,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ bf16_t to_bf16_hw(float v) { return (bf16_t)(pack_bf16x2(v, 0.f) & 0xFFFFu); }
+// v as the sum of two bf16 values: hi = bf16(v), lo = bf16(v - hi)
+__device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
+  hi = to_bf16_hw(v);
+  lo = to_bf16_hw(v - bf16_to_f32(hi));
+}
 
 constexpr int MFMA_MAX_WAVES = 16;   // waves that split K for one tile
 constexpr int AMAX_CELLS = 64;       // selection keys are spread over this many cells per sequence
@@ -61,14 +69,16 @@ __global__ void swizzle_weights_kernel(const bf16_t* __restrict__ W, bf16_t* __r
 struct MfmaArgs {
   const bf16_t* W;       // swizzled [N, K]; SwiGLU: the gate matrix
   const bf16_t* W2;      // SwiGLU: the up matrix
-  const bf16_t* xb;      // packed activations [M, ldxb] (already multiplied by the norm gain if NORM)
+  const bf16_t* xb;      // packed activations, high parts [M, ldxb] (already multiplied by the norm gain if NORM)
+  const bf16_t* xb_lo;   // their low parts, same layout
   int ldxb, M, N, K;
   const float* ssp;      // NORM: partial sums of squares [n_parts, ssp_ld]
   int n_parts, ssp_ld;
   float eps;
   float* y;              // STORE / LOGITS: fp32 out [M, ldy]; RESID: the residual stream, updated in place
   int ldy;
-  bf16_t* yb;            // SwiGLU: packed out [M, ldyb]; RESID: packed input of the next norm (h * g_next)
+  bf16_t* yb;            // SwiGLU: packed out [M, ldyb]; RESID: packed input of the next norm (h * g_next); high parts
+  bf16_t* yb_lo;         // low parts, same layout
   int ldyb;
   const bf16_t* g_next;  // RESID: gain of the next norm [N]
   float* ssp_next;       // RESID: partial sums of squares of the updated residual rows [tiles, ssp_ld]
@@ -76,14 +86,14 @@ struct MfmaArgs {
   int amax_ld;
 };
 
-// BLDS: the block first copies the M packed activation rows into LDS (dynamic shared memory,
-// M * (K + 8) * 2 bytes) and the waves take their B operands from there, which frees the
-// registers a wave would need to hold them; without it each wave loads its B operands from
-// global memory into registers (for M * K too large for LDS).
+// BLDS: the block first copies the M packed activation rows (both planes) into LDS (dynamic shared
+// memory, 2 * M * K * 2 bytes) and the waves take their B operands from there, which frees the
+// registers a wave would need to hold them; without it each wave loads its B operands from global
+// memory into registers, one plane after the other (for M * K too large for LDS).
 template <int EPI, bool NORM, int PF, int NWT, bool BLDS>   // NWT: waves per block (all matrices)
 __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   extern __shared__ float4 dyn_smem[];
-  bf16_t* xs = (bf16_t*)dyn_smem;                        // BLDS: [M][K + 8]
+  bf16_t* xs = (bf16_t*)dyn_smem;                        // BLDS: [2 planes][M][K]
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int nw = NWT / MATS;                         // waves that split K for one matrix
   static_assert(nw >= 1 && nw <= MFMA_MAX_WAVES, "waves per tile");
@@ -104,18 +114,29 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   const bf16_t* __restrict__ abase = (mat == 0 ? a.W : a.W2) + ((size_t)tile * KS) * 1024 + lane * 8;
   const bool colact = r < M;
   const bf16_t* __restrict__ bbase = a.xb + (size_t)(colact ? r : 0) * a.ldxb + kg * 8;
-  const int ldxs = K + 8;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  const bf16_t* __restrict__ bbase_lo = a.xb_lo + (size_t)(colact ? r : 0) * a.ldxb + kg * 8;
+  const int ldxs = K;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = acc;
+  constexpr bool TWO_ACC = BLDS && EPI == EPI_RESID;      // where registers allow (one block per CU)
 
   // small loads first (they return first): the B rows for LDS and the partial sums of squares
   constexpr int NT = 64 * NWT;
-  u32x4 bst[4];
-  const int k8 = K >> 3, n_chunks = M * k8;
+  // registers for the early activation loads: residual projections run one block per CU (few, wide tiles) and can
+  // afford to cover long rows; the others stay within 128 registers (two 8-wave blocks per CU)
+  constexpr int NBST = EPI == EPI_RESID ? 16 : 3;
+  u32x4 bst[NBST];
+  // BLDS requires rows that follow each other in memory (ldxb == K); LDS holds them the same way, the low
+  // plane behind the high one, so a 16-byte chunk's source and destination are linear in its index
+  const int n_chunks = M * (K >> 3);                // 16-byte chunks per plane
+  auto chunk_src = [&](int c) {
+    return (const u32x4*)(c >= n_chunks ? a.xb_lo + (size_t)(c - n_chunks) * 8 : a.xb + (size_t)c * 8);
+  };
+  auto chunk_dst = [&](int c) { return (u32x4*)(xs + (size_t)c * 8); };
   if (BLDS) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int idx = tid + j * NT;
-      if (idx < n_chunks) bst[j] = *(const u32x4*)(a.xb + (size_t)(idx / k8) * a.ldxb + (idx % k8) * 8);
+    for (int j = 0; j < NBST; ++j) {
+      const int c = tid + j * NT;
+      if (c < 2 * n_chunks) bst[j] = *chunk_src(c);
     }
   }
   u32x4 A[PF][2];
@@ -151,48 +172,76 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   }
   if (BLDS) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int idx = tid + j * NT;
-      if (idx < n_chunks) *(u32x4*)(xs + (size_t)(idx / k8) * ldxs + (idx % k8) * 8) = bst[j];
+    for (int j = 0; j < NBST; ++j) {
+      const int c = tid + j * NT;
+      if (c < 2 * n_chunks) *chunk_dst(c) = bst[j];
     }
-    for (int idx = tid + 4 * NT; idx < n_chunks; idx += NT)      // rows beyond what the early loads covered
-      *(u32x4*)(xs + (size_t)(idx / k8) * ldxs + (idx % k8) * 8) = *(const u32x4*)(a.xb + (size_t)(idx / k8) * a.ldxb + (idx % k8) * 8);
+    for (int c = tid + NBST * NT; c < 2 * n_chunks; c += NT) *chunk_dst(c) = *chunk_src(c);   // beyond what the early loads covered
     __syncthreads();
   }
 
   for (int base = s0; base < s1; base += PF) {           // one round unless the wave's k-range exceeds PF steps
     if (base != s0) load_a(base);
-    if (BLDS) {
+    if (BLDS && TWO_ACC) {
+      // registers to spare: both planes of a k-step together, each into its own accumulator, so the
+      // matrix-core work keeps pace with the arriving weights
       const bf16_t* xrow = xs + (size_t)(colact ? r : 0) * ldxs + kg * 8;
+      const bf16_t* xrow_lo = xrow + (size_t)M * ldxs;
 #pragma unroll
       for (int i = 0; i < PF; ++i) {
         const int s = base + i;
-        u32x4 b0 = {0, 0, 0, 0}, b1 = b0;
+        u32x4 b0 = {0, 0, 0, 0}, b1 = b0, c0 = b0, c1 = b0;
         if (s < s1 && colact) {
           b0 = *(const u32x4*)(xrow + (size_t)s * 64);
           b1 = *(const u32x4*)(xrow + (size_t)s * 64 + 32);
+          c0 = *(const u32x4*)(xrow_lo + (size_t)s * 64);
+          c1 = *(const u32x4*)(xrow_lo + (size_t)s * 64 + 32);
         }
+        acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, c0), acc2, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
+        acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, c1), acc2, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
       }
-    } else {
-      u32x4 B[PF][2];
+    } else if (BLDS) {
 #pragma unroll
-      for (int i = 0; i < PF; ++i) {
-        const int s = base + i;
-        B[i][0] = u32x4{0, 0, 0, 0}; B[i][1] = B[i][0];
-        if (s < s1 && colact) {
-          B[i][0] = *(const u32x4*)(bbase + (size_t)s * 64);
-          B[i][1] = *(const u32x4*)(bbase + (size_t)s * 64 + 32);
+      for (int plane = 1; plane >= 0; --plane) {          // low parts first, then the high parts, with the same weights
+        const bf16_t* xrow = xs + ((size_t)plane * M + (colact ? r : 0)) * ldxs + kg * 8;
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+          const int s = base + i;
+          u32x4 b0 = {0, 0, 0, 0}, b1 = b0;
+          if (s < s1 && colact) {
+            b0 = *(const u32x4*)(xrow + (size_t)s * 64);
+            b1 = *(const u32x4*)(xrow + (size_t)s * 64 + 32);
+          }
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
+          if (i & 1) __builtin_amdgcn_sched_barrier(0);   // keeps the LDS reads of later steps from piling up in registers
         }
       }
+    } else {
 #pragma unroll
-      for (int i = 0; i < PF; ++i) {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, B[i][0]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, B[i][1]), acc, 0, 0, 0);
+      for (int plane = 1; plane >= 0; --plane) {          // low parts first, then the high parts, with the same weights
+        const bf16_t* __restrict__ bb = plane ? bbase_lo : bbase;
+        u32x4 B[PF][2];
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+          const int s = base + i;
+          B[i][0] = u32x4{0, 0, 0, 0}; B[i][1] = B[i][0];
+          if (s < s1 && colact) {
+            B[i][0] = *(const u32x4*)(bb + (size_t)s * 64);
+            B[i][1] = *(const u32x4*)(bb + (size_t)s * 64 + 32);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, B[i][0]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, B[i][1]), acc, 0, 0, 0);
+        }
       }
     }
   }
+  if (TWO_ACC) acc += acc2;
   // lane (column r, kg) holds rows kg*4 .. kg*4+3 of column r
   if (colact) {
     red[mat][w][r][kg * 4 + 0] = acc.x; red[mat][w][r][kg * 4 + 1] = acc.y;
@@ -240,12 +289,12 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
 #pragma unroll
         for (int ww = 0; ww < nw; ++ww) v1 += red[MATS - 1][ww][c][row];
         v1 *= rs;
-        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(v0 / (1.0f + __expf(-v0)) * v1);
+        split_bf16(v0 / (1.0f + __expf(-v0)) * v1, a.yb[(size_t)c * a.ldyb + n], a.yb_lo[(size_t)c * a.ldyb + n]);
       } else if (EPI == EPI_RESID) {
         const float hn = hpre[q] + v0;
         a.y[(size_t)c * a.ldy + n] = hn;
         hsq = hn * hn;
-        a.yb[(size_t)c * a.ldyb + n] = to_bf16_hw(hn * gpre[q]);
+        split_bf16(hn * gpre[q], a.yb[(size_t)c * a.ldyb + n], a.yb_lo[(size_t)c * a.ldyb + n]);
       } else {
         a.y[(size_t)c * a.ldy + n] = v0;
         if (EPI == EPI_LOGITS) atomicMax(&key_s[c], argmax_key(v0, n));
@@ -269,16 +318,16 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
 }
 
 // Row-wise helper for the packed path: from an fp32 row h write the packed input of a norm,
-// bf16(h * gain), and the row's sum of squares as a single partial (n_parts = 1).
+// h * gain as high and low bf16 parts, and the row's sum of squares as a single partial (n_parts = 1).
 // Call with all threads of the block; contains a barrier.
 __device__ __forceinline__ void pack_row_for_norm(const float* __restrict__ h, const bf16_t* __restrict__ gain, int d,
-                                                  bf16_t* __restrict__ xb, float* __restrict__ ssp_slot) {
+                                                  bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp_slot) {
   __shared__ float wsum[16];
   float ss = 0.f;
   for (int k = threadIdx.x; k < d; k += blockDim.x) {
     const float v = h[k];
     ss += v * v;
-    xb[k] = to_bf16_hw(v * bf16_to_f32(gain[k]));
+    split_bf16(v * bf16_to_f32(gain[k]), xb[k], xb_lo[k]);
   }
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
@@ -295,36 +344,38 @@ __device__ __forceinline__ void pack_row_for_norm(const float* __restrict__ h, c
 
 __global__ void __launch_bounds__(256) embed_pack_kernel(
     const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset,
-    int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+    int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
+    float* __restrict__ ssp) {
   const int row = blockIdx.x, b = row / r, i = row % r;
   const int pos = row_base(st, sel, offset) + i;
   const bf16_t* src = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* dst = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = bf16_to_f32(src[k]);
-  pack_row_for_norm(dst, gain, d, xb + (size_t)row * d, ssp + row);
+  pack_row_for_norm(dst, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);
 }
 
 __global__ void __launch_bounds__(256) take_last_pack_kernel(
     const float* __restrict__ src, float* __restrict__ dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
     const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset, const bf16_t* __restrict__ gain,
-    bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+    bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp) {
   const int b = blockIdx.x;
   const float* s = src + ((size_t)b * r + (r - 1)) * d;
   float* o = dst + (size_t)b * d;
   const bf16_t* e = nullptr;
   if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + r - 1] * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? bf16_to_f32(e[k]) : 0.0f);
-  pack_row_for_norm(o, gain, d, xb + (size_t)b * d, ssp + b);
+  pack_row_for_norm(o, gain, d, xb + (size_t)b * d, xb_lo + (size_t)b * d, ssp + b);
 }
 
 __global__ void __launch_bounds__(256) add_embed_pack_kernel(
     float* __restrict__ h, const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st,
-    int sel, int offset, int r, int d, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, float* __restrict__ ssp) {
+    int sel, int offset, int r, int d, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
+    float* __restrict__ ssp) {
   const int row = blockIdx.x, b = row / r, i = row % r;
   const bf16_t* e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + i] * d;
   float* o = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += bf16_to_f32(e[k]);
-  pack_row_for_norm(o, gain, d, xb + (size_t)row * d, ssp + row);
+  pack_row_for_norm(o, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);
 }
 
 }  // namespace dmtd
