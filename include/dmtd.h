@@ -142,7 +142,7 @@ int dmtd_read_kv(dmtd_ctx* ctx, int32_t layer, int32_t b, int32_t n_pos, float* 
  * in microseconds.  Activations are whatever the workspace holds; caches, token history and
  * scheduler state are not modified (the residual stream scratch is).  kind: DMTD_K_*.
  * Needs a prefilled context (attention reads the current context length).
- * Errors: DMTD_EINVAL (kind, rows outside [1, 16], reps < 1), DMTD_ESTATE, DMTD_EHIP. */
+ * Errors: DMTD_EINVAL (kind, rows outside [1, 16] for attention (rows per sequence) or [1, 16 * max_batch] for the projections (total rows), reps < 1), DMTD_ESTATE, DMTD_EHIP. */
 #define DMTD_K_QKV     0   /* RMSNorm + fused QKV projection (Sec. 3.1 model; hot-path step a2) */
 #define DMTD_K_OPROJ   1   /* O projection + residual */
 #define DMTD_K_GATEUP  2   /* RMSNorm + gate/up projections + SwiGLU */

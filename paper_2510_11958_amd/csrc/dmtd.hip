@@ -31,7 +31,8 @@ constexpr int kMaxTau = 64;          // steps per decode call (size of the emitt
 constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming pass
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
-constexpr int kMfmaRows = 16;        // activation rows per MFMA weight-streaming pass
+constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
+constexpr int kGemmRows = 64;        // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 constexpr int kMfmaPFGateUp = 8;     // the same for gate/up: with the two activation planes 10 steps no longer fit 128 registers (two blocks per CU)
 constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter runs put 8 waves on a tile (measured 8.3 us instead of 9.3 us at 4B shapes)
@@ -50,6 +51,7 @@ struct Ws {   // device workspace carve-up (byte offsets)
   size_t h, h_late, qkv, attn, mlp, logits, part_o, part_ml, amax;
   size_t tokens, emitted, forced, state, inv_freq, rope_tab;
   size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
+  size_t gemm_part;                            // K-split partial sums of the tiled kernel
   size_t total;
 };
 
@@ -157,6 +159,11 @@ Ws layout(const dmtd_config& c) {
     w.xb_late = take(B * d * 2 * 2);
     w.ssp = take(parts * rows * 4);
     w.ssp_late = take(parts * rows * 4);
+    {
+      size_t widest = 2 * (size_t)c.intermediate > nqkv ? 2 * (size_t)c.intermediate : nqkv;
+      if (d > widest) widest = d;
+      w.gemm_part = take((size_t)8 * kGemmRows * widest * 4);
+    }
     w.wsw = take((swizzled_layer_elems(c) * c.n_layers + swizzled_elems(c.vocab, d)) * 2);
   }
   w.total = off;
@@ -245,7 +252,7 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
 
 // nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4, 5}) that lets a wave
 // hold its k-range in one round of PF k-steps, else the largest with several rounds.
-// Rows beyond 16 go in further launches (each streams the matrix again).
+// More than 16 rows go through the LDS-tiled kernel, 64 per pass (each pass streams the matrix once).
 template <int EPI, bool NORM, int PF = kMfmaPF>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
@@ -254,6 +261,51 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   int nw = 2;
   while (nw < nw_max && (KS + nw - 1) / nw > PF) nw = (EPI == EPI_SWIGLU && nw == 4) ? 5 : nw * 2;
   const dim3 grid((a.N + 15) / 16);
+  // The one-tile-per-block kernel keeps all rows (both planes) in LDS: comfortably (two blocks per CU) in general,
+  // up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway.  Rows that do not
+  // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to 64 rows.
+  const size_t lds_rows = (size_t)2 * (rows < kMfmaRows ? rows : kMfmaRows) * a.K * 2;
+  const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
+  if (!fits) {
+    const int n_tiles = (a.N + 15) / 16;
+    const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + GEMM_WAVES - 1) / GEMM_WAVES : (n_tiles + GEMM_TILES_PER_BLOCK - 1) / GEMM_TILES_PER_BLOCK);
+    for (int m0 = 0; m0 < rows; m0 += kGemmRows) {
+      MfmaArgs g = a;
+      g.M = rows - m0 < kGemmRows ? rows - m0 : kGemmRows;
+      g.xb = a.xb + (size_t)m0 * a.ldxb;
+      g.xb_lo = a.xb_lo + (size_t)m0 * a.ldxb;
+      if (a.ssp) g.ssp = a.ssp + m0;
+      if (a.y) g.y = a.y + (size_t)m0 * a.ldy;
+      if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
+      if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
+      if (a.amax) g.amax = a.amax + m0;
+      // enough k-steps in flight for HBM: about 2048 (tile, split) streams; the LM head has them without splitting
+      const int KS = a.K / 64;
+      int ksplit = 1;
+      if constexpr (EPI != EPI_LOGITS) {
+        ksplit = (2048 + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
+        if (ksplit > 8) ksplit = 8;
+        if (ksplit > KS / 3) ksplit = KS / 3 > 0 ? KS / 3 : 1;
+      }
+      if (ksplit > 1) {
+        if constexpr (EPI != EPI_LOGITS) {
+          g.ksplit = ksplit;
+          g.ldp = (EPI == EPI_SWIGLU ? 2 : 1) * a.N;
+          g.part = (float*)(c->ws + c->o.gemm_part);
+          const dim3 sgrid(ggrid.x, ksplit);
+          if (g.M <= 16) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+          else if (g.M <= 32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+          hipLaunchKernelGGL((gemm_finish_kernel<EPI, NORM>), dim3((a.N / 4 + 255) / 256, g.M), dim3(256), 0, c->stream, g);
+        }
+      } else {
+        if (g.M <= 16) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+        else if (g.M <= 32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+      }
+    }
+    return hipGetLastError();
+  }
   for (int m0 = 0; m0 < rows; m0 += kMfmaRows) {
     MfmaArgs g = a;
     g.M = rows - m0 < kMfmaRows ? rows - m0 : kMfmaRows;
@@ -264,22 +316,17 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
     if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
     if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
     if (a.amax) g.amax = a.amax + m0;
-    // B operands (both planes) through LDS when the packed rows fit: comfortably (two blocks per CU) in
-    // general, up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway
-    const size_t lds = (size_t)2 * g.M * a.K * 2;
-    const bool blds = a.ldxb == a.K && lds <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
-#define DMTD_LAUNCH_MFMA(NWT_)                                                                                              \
-    do {                                                                                                                    \
-      if (blds) {                                                                                                           \
-        auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>;                                                            \
-        static bool big_lds = false;                                                                                        \
-        if (lds > 48 * 1024 && !big_lds) {                                                                                  \
-          hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);   \
-          if (ae != hipSuccess) return ae;                                                                                  \
-          big_lds = true;                                                                                                   \
-        }                                                                                                                   \
-        hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g);                                                 \
-      } else hipLaunchKernelGGL((gemv_mfma_kernel<EPI, NORM, PF, NWT_, false>), grid, dim3(64 * NWT_), 0, c->stream, g);    \
+    const size_t lds = (size_t)2 * g.M * a.K * 2;      // the rows, both planes
+#define DMTD_LAUNCH_MFMA(NWT_)                                                                                            \
+    do {                                                                                                                  \
+      auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>;                                                            \
+      static bool big_lds = false;                                                                                        \
+      if (lds > 48 * 1024 && !big_lds) {                                                                                  \
+        hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);   \
+        if (ae != hipSuccess) return ae;                                                                                  \
+        big_lds = true;                                                                                                   \
+      }                                                                                                                   \
+      hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g);                                                 \
     } while (0)
     if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
     else if (nw == 4) DMTD_LAUNCH_MFMA(4 * MATS);
@@ -954,7 +1001,9 @@ int dmtd_read_kv(dmtd_ctx* c, int32_t layer, int32_t b, int32_t n_pos, float* ou
 
 int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, float* avg_us) {
   if (!c) return DMTD_EINVAL;
-  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > kMaxRows || reps < 1) {
+  // attention: rows per sequence (at most 16); projections: total activation rows (at most max_batch * 16, the row buffers' capacity)
+  const int rows_max = kind == DMTD_K_ATTN ? kMaxRows : c->cfg.max_batch * kMaxRows;
+  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > rows_max || reps < 1) {
     c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
   }
   if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }

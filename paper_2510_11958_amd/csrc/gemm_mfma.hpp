@@ -1,0 +1,290 @@
+// Weight-streaming projection for 17..64 activation rows of a bf16 model on gfx950 (batched
+// decode steps, refill rows of several sequences, prefill of a batch): the rows form CG groups
+// of 16 MFMA columns and ONE pass over the weights serves them all.
+//
+// With this many rows the activations no longer fit in LDS whole, and a block that owned one
+// 16-row weight tile (as the 1..16-row kernel does) would pull every activation through L2 again
+// for every tile.  Here a block of 4 waves owns 8 weight tiles (2 per wave; SwiGLU: the gate and
+// the up tile of the same 16 outputs) and walks K in steps of 64:
+//   * weights: operand-order tiles straight from HBM into registers, 3 k-steps ahead per wave;
+//   * activations: the k-step's slice of all rows, both bf16 planes (see gemv_mfma.hpp), fetched
+//     by all threads 3 k-steps ahead into registers, written to one of two LDS buffers and shared
+//     by the block's 8 tiles, every B fragment feeding the matrix cores twice (one per tile of a wave).
+// One block barrier per k-step.  A wave owns its tiles over the block's whole k-range, so nothing is
+// reduced across waves.
+//
+// Memory-level parallelism: a tile has 3 k-steps (6 KiB) in flight, so a projection with few tiles
+// (QKV 384, O and down 160 at 4B shapes) would keep only 1-2 MB in flight, far below what HBM needs
+// (about 12 MB).  Such launches split K over gridDim.y blocks; each stores its raw partial tile sums,
+// and gemm_finish_kernel adds them in order and runs the epilogue.  The LM head (thousands of tiles)
+// runs unsplit with the epilogue in this kernel.
+#pragma once
+#include "gemv_mfma.hpp"
+
+namespace dmtd {
+
+constexpr int GEMM_WAVES = 4;
+constexpr int GEMM_TILES_PER_BLOCK = 8;     // weight tiles of 16 outputs a block owns (SwiGLU: 4 gate + 4 up)
+
+template <int EPI, bool NORM, int CG, bool SPLITK>
+__global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) {
+  constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
+  constexpr int PF = 3;                  // k-steps in flight
+  constexpr int LDB = 72;                // LDS row: 64 values + 8 of padding
+  constexpr int NT = 64 * GEMM_WAVES;
+  constexpr int PIECES = 2 * BM * 8;     // 16-byte pieces of one k-step's activation slice (2 planes)
+  constexpr int PPT = PIECES / NT;       // per thread
+  static_assert(PIECES % NT == 0, "pieces per thread");
+  __shared__ __attribute__((aligned(16))) bf16_t bs[2][2][BM][LDB];    // [buffer][plane][row][k]
+  __shared__ float rs_s[BM];
+  __shared__ unsigned long long key_s[BM];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 15, kg = lane >> 4;
+  const int M = a.M, N = a.N, K = a.K, KS = K >> 6;
+  const int n_tiles = (N + 15) >> 4;
+  // this block's k-steps
+  const int s_lo = SPLITK ? (int)((long)blockIdx.y * KS / a.ksplit) : 0;
+  const int s_hi = SPLITK ? (int)((long)(blockIdx.y + 1) * KS / a.ksplit) : KS;
+
+  int tile[2];
+  const bf16_t* wp[2];
+  if (EPI == EPI_SWIGLU) {
+    tile[0] = tile[1] = blockIdx.x * GEMM_WAVES + w;
+    wp[0] = a.W; wp[1] = a.W2;
+  } else {
+    tile[0] = (blockIdx.x * GEMM_WAVES + w) * 2; tile[1] = tile[0] + 1;
+    wp[0] = wp[1] = a.W;
+  }
+  const bool tv[2] = {tile[0] < n_tiles, tile[1] < n_tiles};
+  const bf16_t* abase[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) abase[j] = wp[j] + ((size_t)(tv[j] ? tile[j] : 0) * KS) * 1024 + lane * 8;
+
+  // this thread's pieces of an activation slice: piece q = (plane, row, 16-byte column c8); rows beyond M repeat row M-1
+  // (their MFMA columns are never stored)
+  const bf16_t* bsrc[PPT];
+  int bdst[PPT];
+#pragma unroll
+  for (int i = 0; i < PPT; ++i) {
+    const int q = tid + i * NT, plane = q / (BM * 8), row = (q >> 3) % BM, c8 = q & 7;
+    bsrc[i] = (plane ? a.xb_lo : a.xb) + (size_t)min(row, M - 1) * a.ldxb + c8 * 8;
+    bdst[i] = (plane * BM + row) * LDB + c8 * 8;
+  }
+
+  u32x4 A[PF][2][2];     // [slot][tile][half of the k-step]
+  u32x4 Bq[PF][PPT];
+  auto issue = [&](int s, int slot) {      // slot is a compile-time constant at every call
+    if (s < s_hi) {
+#pragma unroll
+      for (int i = 0; i < PPT; ++i) Bq[slot][i] = *(const u32x4*)(bsrc[i] + (size_t)s * 64);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        A[slot][j][0] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024));
+        A[slot][j][1] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024 + 512));
+      }
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s) issue(s_lo + s, s);
+
+  f32x4 acc[2][CG];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int g = 0; g < CG; ++g) acc[j][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  auto step = [&](int s, int slot) {
+    bf16_t* buf = &bs[s & 1][0][0][0];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) *(u32x4*)(buf + bdst[i]) = Bq[slot][i];
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+#pragma unroll
+      for (int plane = 1; plane >= 0; --plane) {
+        const bf16_t* row = buf + (plane * BM + g * 16 + r) * LDB + kg * 8;
+        const bf16x8_t b0 = __builtin_bit_cast(bf16x8_t, *(const u32x4*)row);
+        const bf16x8_t b1 = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(row + 32));
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[j][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[slot][j][0]), b0, acc[j][g], 0, 0, 0);
+          acc[j][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[slot][j][1]), b1, acc[j][g], 0, 0, 0);
+        }
+      }
+    }
+    issue(s + PF, slot);
+  };
+  for (int s0 = s_lo; s0 < s_hi; s0 += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+      if (s0 + u < s_hi) step(s0 + u, u);
+  }
+
+  if (SPLITK) {
+    // raw partial sums: part[split][m][n] (SwiGLU: the up tile's outputs at N + n)
+    float* part = a.part + (size_t)blockIdx.y * M * a.ldp;
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+      const int m = g * 16 + r;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (m < M && tv[j]) {
+          const int n0 = tile[j] * 16 + kg * 4 + ((EPI == EPI_SWIGLU && j == 1) ? N : 0);
+          *(float4*)(part + (size_t)m * a.ldp + n0) = make_float4(acc[j][g][0], acc[j][g][1], acc[j][g][2], acc[j][g][3]);
+        }
+      }
+    }
+    return;
+  }
+
+  // ---- epilogue: lane (column r of group g = activation row g*16 + r, kg) holds outputs tile*16 + kg*4 + 0..3
+  if (tid < BM) key_s[tid] = 0ull;
+  if (NORM) {
+    if (tid < M) {
+      float s = 0.f;
+      for (int p = 0; p < a.n_parts; ++p) s += a.ssp[(size_t)p * a.ssp_ld + tid];
+      rs_s[tid] = rsqrtf(s / (float)K + a.eps);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < CG; ++g) {
+    const int m = g * 16 + r;
+    const bool mact = m < M;
+    const float rs = (NORM && mact) ? rs_s[m] : 1.f;
+    if (EPI == EPI_SWIGLU) {
+      const int n0 = tile[0] * 16 + kg * 4;
+      if (mact && tv[0]) {
+        float u[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const float gt = acc[0][g][jj] * rs, up = acc[1][g][jj] * rs;
+          u[jj] = gt / (1.0f + __expf(-gt)) * up;
+        }
+        bf16_t hi[4], lo[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) split_bf16(u[jj], hi[jj], lo[jj]);
+        *(uint2*)(a.yb + (size_t)m * a.ldyb + n0) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+        *(uint2*)(a.yb_lo + (size_t)m * a.ldyb + n0) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n0 = tile[j] * 16 + kg * 4;
+        float hsq = 0.f;
+        unsigned long long best = 0ull;
+        if (mact && tv[j]) {
+          float v[4];
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) v[jj] = acc[j][g][jj] * rs;
+          if (EPI == EPI_RESID) {
+            float4 h4 = *(const float4*)(a.y + (size_t)m * a.ldy + n0);
+            h4.x += v[0]; h4.y += v[1]; h4.z += v[2]; h4.w += v[3];
+            *(float4*)(a.y + (size_t)m * a.ldy + n0) = h4;
+            const float hn[4] = {h4.x, h4.y, h4.z, h4.w};
+            bf16_t hi[4], lo[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              hsq += hn[jj] * hn[jj];
+              split_bf16(hn[jj] * bf16_to_f32(a.g_next[n0 + jj]), hi[jj], lo[jj]);
+            }
+            *(uint2*)(a.yb + (size_t)m * a.ldyb + n0) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+            *(uint2*)(a.yb_lo + (size_t)m * a.ldyb + n0) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+          } else {
+            if (n0 + 3 < N) {
+              *(float4*)(a.y + (size_t)m * a.ldy + n0) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj)
+                if (n0 + jj < N) a.y[(size_t)m * a.ldy + n0 + jj] = v[jj];
+            }
+            if (EPI == EPI_LOGITS) {
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj)
+                if (n0 + jj < N) { const unsigned long long k = argmax_key(v[jj], n0 + jj); if (k > best) best = k; }
+            }
+          }
+        }
+        if (EPI == EPI_RESID) {
+          // sum of squares of the 16 outputs of this tile for activation row m: over the 4 kg lanes
+          hsq += __shfl_xor(hsq, 16, 64);
+          hsq += __shfl_xor(hsq, 32, 64);
+          if (mact && tv[j] && kg == 0) a.ssp_next[(size_t)tile[j] * a.ssp_ld + m] = hsq;
+        }
+        if (EPI == EPI_LOGITS && best != 0ull) atomicMax(&key_s[m], best);
+      }
+    }
+  }
+  if (EPI == EPI_LOGITS) {
+    __syncthreads();
+    if (tid < M && key_s[tid] != 0ull) atomicMax(a.amax + (size_t)(blockIdx.x % AMAX_CELLS) * a.amax_ld + tid, key_s[tid]);
+  }
+}
+
+// Second stage of a K-split launch: out = epilogue(sum over the splits, in order).  One thread per
+// (activation row m, 4 consecutive outputs); a block covers 1024 outputs of one row.
+template <int EPI, bool NORM>
+__global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
+  __shared__ float red_s[4];
+  __shared__ float rs_sh;
+  const int m = blockIdx.y, tid = threadIdx.x;
+  const int n0 = (blockIdx.x * 256 + tid) * 4;
+  const int N = a.N, M = a.M;
+  float rs = 1.f;
+  if (NORM) {
+    float s = 0.f;
+    for (int p = tid; p < a.n_parts; p += 256) s += a.ssp[(size_t)p * a.ssp_ld + m];
+    s = wave_sum(s);
+    if ((tid & 63) == 0) red_s[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) rs_sh = rsqrtf((red_s[0] + red_s[1] + red_s[2] + red_s[3]) / (float)a.K + a.eps);
+    __syncthreads();
+    rs = rs_sh;
+  }
+  const bool act = n0 < N;      // N is a multiple of 16 on this path
+  float v[4] = {0.f, 0.f, 0.f, 0.f}, v2[4] = {0.f, 0.f, 0.f, 0.f};
+  if (act) {
+    for (int ks = 0; ks < a.ksplit; ++ks) {
+      const float* p = a.part + ((size_t)ks * M + m) * a.ldp + n0;
+      const float4 x = *(const float4*)p;
+      v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
+      if (EPI == EPI_SWIGLU) {
+        const float4 y = *(const float4*)(p + N);
+        v2[0] += y.x; v2[1] += y.y; v2[2] += y.z; v2[3] += y.w;
+      }
+    }
+  }
+  float hsq = 0.f;
+  if (act) {
+    float o[4];
+    if (EPI == EPI_STORE) {
+      *(float4*)(a.y + (size_t)m * a.ldy + n0) = make_float4(v[0] * rs, v[1] * rs, v[2] * rs, v[3] * rs);
+    } else {
+      if (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) { const float gt = v[jj] * rs; o[jj] = gt / (1.0f + __expf(-gt)) * (v2[jj] * rs); }
+      } else {
+        float4 h4 = *(const float4*)(a.y + (size_t)m * a.ldy + n0);
+        h4.x += v[0]; h4.y += v[1]; h4.z += v[2]; h4.w += v[3];
+        *(float4*)(a.y + (size_t)m * a.ldy + n0) = h4;
+        const float hn[4] = {h4.x, h4.y, h4.z, h4.w};
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) { hsq += hn[jj] * hn[jj]; o[jj] = hn[jj] * bf16_to_f32(a.g_next[n0 + jj]); }
+      }
+      bf16_t hi[4], lo[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) split_bf16(o[jj], hi[jj], lo[jj]);
+      *(uint2*)(a.yb + (size_t)m * a.ldyb + n0) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+      *(uint2*)(a.yb_lo + (size_t)m * a.ldyb + n0) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+    }
+  }
+  if (EPI == EPI_RESID) {
+    // sum of squares per tile of 16 outputs: the 4 neighbouring threads of a tile
+    hsq += __shfl_xor(hsq, 1, 64);
+    hsq += __shfl_xor(hsq, 2, 64);
+    if (act && (tid & 3) == 0) a.ssp_next[(size_t)(n0 >> 4) * a.ssp_ld + m] = hsq;
+  }
+}
+
+}  // namespace dmtd

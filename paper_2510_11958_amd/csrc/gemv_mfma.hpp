@@ -84,6 +84,8 @@ struct MfmaArgs {
   float* ssp_next;       // RESID: partial sums of squares of the updated residual rows [tiles, ssp_ld]
   unsigned long long* amax;   // LOGITS: selection keys [AMAX_CELLS, amax_ld], already offset to this launch's rows
   int amax_ld;
+  float* part;           // tiled kernel with K split over blocks: partial sums [ksplit][M][ldp]
+  int ksplit, ldp;
 };
 
 // BLDS: the block first copies the M packed activation rows (both planes) into LDS (dynamic shared

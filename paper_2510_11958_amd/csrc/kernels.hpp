@@ -200,5 +200,6 @@ __global__ void add_embed_rows_kernel(float* __restrict__ h, const WT* __restric
 
 #include "gemv.hpp"
 #include "gemv_mfma.hpp"
+#include "gemm_mfma.hpp"
 #include "attention.hpp"
 #include "attention_mfma.hpp"

@@ -164,7 +164,10 @@ def test_batch_rows_are_independent_and_identical_prompts_agree(model_4b):
     solo.prefill(prompts[1:2])
     souts = np.concatenate([solo.decode_cycle(3, 8) for _ in range(3)], 1)
     assert np.array_equal(souts[0], toks[1])
-    assert np.abs(solo.logits()[0] - z[1]).max() <= 1e-3 * np.abs(z[1]).max()
+    # alone, the sequence runs through the kernels for few rows (K split over waves), in the batch through the
+    # tiled kernel for many rows (K in order): fp32 sums differ in the last bits, some bf16 cache entries round the
+    # other way, and 36 layers later the logits differ at the level of the bf16 noise, well inside the tolerance
+    assert np.abs(solo.logits()[0] - z[1]).max() <= 0.5 * TOL_BF16 * np.abs(z[1]).max()
 
 
 def test_long_context_attention_one_layer():
