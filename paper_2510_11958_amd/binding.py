@@ -43,6 +43,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it first (python -m paper_2510_11958_amd.build); "
                           "there is no fallback path")
+    # PyTorch ships its own HIP runtime: load it first, so that the library binds to the runtime that owns the
+    # device memory it is handed (loading the system runtime first leaves the process with two of them)
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     P = C.POINTER
     lib.dmtd_workspace_bytes.restype = C.c_size_t

@@ -319,7 +319,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
     const size_t lds = (size_t)2 * g.M * a.K * 2;      // the rows, both planes
 #define DMTD_LAUNCH_MFMA(NWT_)                                                                                            \
     do {                                                                                                                  \
-      auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_, true>;                                                            \
+      auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_>;                                                            \
       static bool big_lds = false;                                                                                        \
       if (lds > 48 * 1024 && !big_lds) {                                                                                  \
         hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);   \

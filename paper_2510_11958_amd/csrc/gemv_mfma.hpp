@@ -88,14 +88,13 @@ struct MfmaArgs {
   int ksplit, ldp;
 };
 
-// BLDS: the block first copies the M packed activation rows (both planes) into LDS (dynamic shared
-// memory, 2 * M * K * 2 bytes) and the waves take their B operands from there, which frees the
-// registers a wave would need to hold them; without it each wave loads its B operands from global
-// memory into registers, one plane after the other (for M * K too large for LDS).
-template <int EPI, bool NORM, int PF, int NWT, bool BLDS>   // NWT: waves per block (all matrices)
+// The block first copies the M packed activation rows (both planes) into LDS (dynamic shared
+// memory, 2 * M * K * 2 bytes) and the waves take their B operands from there; the host sends rows
+// that do not fit there to the LDS-tiled kernel (gemm_mfma.hpp).
+template <int EPI, bool NORM, int PF, int NWT>   // NWT: waves per block (all matrices)
 __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   extern __shared__ float4 dyn_smem[];
-  bf16_t* xs = (bf16_t*)dyn_smem;                        // BLDS: [2 planes][M][K]
+  bf16_t* xs = (bf16_t*)dyn_smem;                        // [2 planes][M][K]
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int nw = NWT / MATS;                         // waves that split K for one matrix
   static_assert(nw >= 1 && nw <= MFMA_MAX_WAVES, "waves per tile");
@@ -115,11 +114,9 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
 
   const bf16_t* __restrict__ abase = (mat == 0 ? a.W : a.W2) + ((size_t)tile * KS) * 1024 + lane * 8;
   const bool colact = r < M;
-  const bf16_t* __restrict__ bbase = a.xb + (size_t)(colact ? r : 0) * a.ldxb + kg * 8;
-  const bf16_t* __restrict__ bbase_lo = a.xb_lo + (size_t)(colact ? r : 0) * a.ldxb + kg * 8;
   const int ldxs = K;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = acc;
-  constexpr bool TWO_ACC = BLDS && EPI == EPI_RESID;      // where registers allow (one block per CU)
+  constexpr bool TWO_ACC = EPI == EPI_RESID;      // where registers allow (one block per CU)
 
   // small loads first (they return first): the B rows for LDS and the partial sums of squares
   constexpr int NT = 64 * NWT;
@@ -127,19 +124,17 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   // afford to cover long rows; the others stay within 128 registers (two 8-wave blocks per CU)
   constexpr int NBST = EPI == EPI_RESID ? 16 : 3;
   u32x4 bst[NBST];
-  // BLDS requires rows that follow each other in memory (ldxb == K); LDS holds them the same way, the low
+  // the rows follow each other in memory (ldxb == K); LDS holds them the same way, the low
   // plane behind the high one, so a 16-byte chunk's source and destination are linear in its index
   const int n_chunks = M * (K >> 3);                // 16-byte chunks per plane
   auto chunk_src = [&](int c) {
     return (const u32x4*)(c >= n_chunks ? a.xb_lo + (size_t)(c - n_chunks) * 8 : a.xb + (size_t)c * 8);
   };
   auto chunk_dst = [&](int c) { return (u32x4*)(xs + (size_t)c * 8); };
-  if (BLDS) {
 #pragma unroll
-    for (int j = 0; j < NBST; ++j) {
-      const int c = tid + j * NT;
-      if (c < 2 * n_chunks) bst[j] = *chunk_src(c);
-    }
+  for (int j = 0; j < NBST; ++j) {
+    const int c = tid + j * NT;
+    if (c < 2 * n_chunks) bst[j] = *chunk_src(c);
   }
   u32x4 A[PF][2];
   auto load_a = [&](int base) {
@@ -172,19 +167,17 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
     const int n_items = M * a.n_parts;
     for (int i = tid; i < n_items && i < SS_ITEMS; i += NT) ss_items[i] = a.ssp[(size_t)(i / M) * a.ssp_ld + (i % M)];
   }
-  if (BLDS) {
 #pragma unroll
-    for (int j = 0; j < NBST; ++j) {
-      const int c = tid + j * NT;
-      if (c < 2 * n_chunks) *chunk_dst(c) = bst[j];
-    }
-    for (int c = tid + NBST * NT; c < 2 * n_chunks; c += NT) *chunk_dst(c) = *chunk_src(c);   // beyond what the early loads covered
-    __syncthreads();
+  for (int j = 0; j < NBST; ++j) {
+    const int c = tid + j * NT;
+    if (c < 2 * n_chunks) *chunk_dst(c) = bst[j];
   }
+  for (int c = tid + NBST * NT; c < 2 * n_chunks; c += NT) *chunk_dst(c) = *chunk_src(c);   // beyond what the early loads covered
+  __syncthreads();
 
   for (int base = s0; base < s1; base += PF) {           // one round unless the wave's k-range exceeds PF steps
     if (base != s0) load_a(base);
-    if (BLDS && TWO_ACC) {
+    if (TWO_ACC) {
       // registers to spare: both planes of a k-step together, each into its own accumulator, so the
       // matrix-core work keeps pace with the arriving weights
       const bf16_t* xrow = xs + (size_t)(colact ? r : 0) * ldxs + kg * 8;
@@ -204,7 +197,7 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
         acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, c1), acc2, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
       }
-    } else if (BLDS) {
+    } else {
 #pragma unroll
       for (int plane = 1; plane >= 0; --plane) {          // low parts first, then the high parts, with the same weights
         const bf16_t* xrow = xs + ((size_t)plane * M + (colact ? r : 0)) * ldxs + kg * 8;
@@ -219,26 +212,6 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
           if (i & 1) __builtin_amdgcn_sched_barrier(0);   // keeps the LDS reads of later steps from piling up in registers
-        }
-      }
-    } else {
-#pragma unroll
-      for (int plane = 1; plane >= 0; --plane) {          // low parts first, then the high parts, with the same weights
-        const bf16_t* __restrict__ bb = plane ? bbase_lo : bbase;
-        u32x4 B[PF][2];
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-          const int s = base + i;
-          B[i][0] = u32x4{0, 0, 0, 0}; B[i][1] = B[i][0];
-          if (s < s1 && colact) {
-            B[i][0] = *(const u32x4*)(bb + (size_t)s * 64);
-            B[i][1] = *(const u32x4*)(bb + (size_t)s * 64 + 32);
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, B[i][0]), acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, B[i][1]), acc, 0, 0, 0);
         }
       }
     }
