@@ -29,6 +29,11 @@ design notes):
     prompt and the token emitted by prefill is the first token of cycle 1 (Sec. 2.2).
   * Refill rows are causal among themselves and carry their true absolute positions.
   * Greedy selection, lowest index among equal maxima.
+  * ExDy variant (Sec. 2.1, last paragraph before Eq. 5; Sec. 3.3): with ``n_early = x`` the
+    in-cycle positions feed the decoding layers the output of the first ``x`` (encoding)
+    layers instead of the raw embedding; tokens inside a cycle run those ``x`` layers and
+    then jump to the last ``y``; only the thinking layers in between are refilled, from the
+    stored encoding outputs.  ``n_early = 0`` is the plain method.
 
 Pins: the vanilla path is checked against the Hugging Face Qwen3 implementation and
 against an independent brute-force recompute; the cycle machine against the one-shot
@@ -210,26 +215,32 @@ def inference_mask(n: int, prompt_len: int, tau: int) -> np.ndarray:
     return (p < prompt_len) | ((p - (prompt_len - 1)) % tau == 0)
 
 
-def masked_forward(tokens, mask, n_late: int, w: dict, cfg: OracleConfig) -> np.ndarray:
+def masked_forward(tokens, mask, n_late: int, w: dict, cfg: OracleConfig, n_early: int = 0) -> np.ndarray:
     """Eqs. 1-5 as one causal pass over ``tokens``; returns logits ``[n, V]``.
 
-    Front layers (encoding + thinking, the first ``L - n_late``) run on every
-    position; the late (decoding) layers read, at position ``i``, the front output
-    where ``mask[i]`` and the raw embedding elsewhere (Eq. 4).  With
-    ``cfg.full_pos_add_embed`` full positions read ``h_emb + h_think`` instead.
+    Encoding layers (the first ``n_early``, Eq. 1) and thinking layers (up to layer
+    ``L - n_late``, Eq. 2) run on every position; the late (decoding) layers read, at
+    position ``i``, the thinking output where ``mask[i]`` and, elsewhere, the raw embedding
+    (Eq. 4) or, in the ExDy variant, the encoding output.  With ``cfg.full_pos_add_embed``
+    full positions read ``h_emb + h_think`` (ExDy: ``h_enc + h_think``) instead.
     """
     tokens = np.asarray(tokens)
     mask = np.asarray(mask, dtype=bool)
     h_emb = w["embed"][tokens]
     front = cfg.n_layers - n_late
+    if not (0 <= n_early <= front):
+        raise ValueError("n_early must lie in [0, L - n_late]")
     h = h_emb
-    for l in range(front):
+    for l in range(n_early):
         h = block_full_sequence(w["layers"][l], h, cfg)
-    h_think = h
+    h_enc = h                                    # Eq. 1 (the embedding itself when n_early = 0)
+    for l in range(n_early, front):
+        h = block_full_sequence(w["layers"][l], h, cfg)
+    h_think = h                                  # Eq. 2
     if cfg.full_pos_add_embed:
-        h_masked = h_emb + h_think * mask[:, None]
+        h_masked = h_enc + h_think * mask[:, None]
     else:
-        h_masked = np.where(mask[:, None], h_think, h_emb)
+        h_masked = np.where(mask[:, None], h_think, h_enc)
     h = h_masked
     for l in range(front, cfg.n_layers):
         h = block_full_sequence(w["layers"][l], h, cfg)
@@ -242,9 +253,10 @@ def vanilla_forward(tokens, w: dict, cfg: OracleConfig) -> np.ndarray:
     return masked_forward(tokens, np.ones(len(tokens), bool), cfg.n_layers, w, cfg0)
 
 
-def plt_closed_form(n_layers: int, n_late: int, tau: int) -> float:
-    """Eq. 7: (L + (tau - 1) L_d) / (tau L)."""
-    return (n_layers + (tau - 1) * n_late) / (tau * n_layers)
+def plt_closed_form(n_layers: int, n_late: int, tau: int, n_early: int = 0) -> float:
+    """Eq. 7: (L + (tau - 1) L_d) / (tau L); in the ExDy variant the in-cycle tokens also pass
+    the ``n_early`` encoding layers, so L_d becomes ``n_early + n_late`` layers per in-cycle token."""
+    return (n_layers + (tau - 1) * (n_early + n_late)) / (tau * n_layers)
 
 
 # -------------------------------------------------------- incremental cycle machine
@@ -278,6 +290,8 @@ class DmtdOracle:
         self.refill_layer_visits = 0      # layers traversed by refill rows
         self.n_emitted = 0                # tokens emitted by decode steps (prefill's excluded)
         self.n_late_in_use = None
+        self.n_early_in_use = 0
+        self.pend_enc: list[np.ndarray] = []   # ExDy: encoding outputs of the tokens that await refill
 
     # one block over `rows` new positions with the layer's cache
     def _block(self, l: int, X: np.ndarray, positions: np.ndarray) -> np.ndarray:
@@ -295,11 +309,12 @@ class DmtdOracle:
         self.step_logits.append(z)
         return int(np.argmax(z))
 
-    def prefill(self, tokens, n_late: int | None = None) -> int:
+    def prefill(self, tokens, n_late: int | None = None, n_early: int = 0) -> int:
         """All prompt tokens through all layers; returns the first generated token.
 
-        ``n_late`` matters only under the literal Eq. 4 reading, where the embedding is
-        added again at the front/late boundary of every (full) prompt position.
+        ``n_late`` (and ``n_early``) matter only under the literal Eq. 4 reading, where the
+        embedding (ExDy: the encoding output) is added again at the front/late boundary of
+        every (full) prompt position.
         """
         tokens = [int(t) for t in tokens]
         P = len(tokens)
@@ -314,58 +329,77 @@ class DmtdOracle:
         E = self.w["embed"][np.asarray(tokens)]
         H = E
         F = c.n_layers - (n_late if n_late is not None else 0)
+        base = E
         for l in range(c.n_layers):
+            if l == n_early:
+                base = H                                 # Eq. 1 output (the embedding when n_early = 0)
             if l == F and c.full_pos_add_embed:
-                H = H + E
+                H = H + base
             H = self._block(l, H, pos)
         self.tokens = tokens
         self.trace.append([("front", list(range(P))), ("late", list(range(P)))])
         self.n_tok = self.n_front = P
         self.phase = 1
         self.n_late_in_use = n_late
+        self.n_early_in_use = n_early
         self.last = self._emit(H[-1])
         return self.last
 
-    def _late_step(self, n_late: int) -> int:
+    def _late_step(self, n_late: int, n_early: int = 0) -> int:
         c = self.cfg
         F = c.n_layers - n_late
         p = self.n_tok
         self.tokens.append(self.last)
         h = self.w["embed"][self.last][None, :]          # Eq. 4, m = 0: raw embedding
         pos = np.array([p])
+        for l in range(n_early):
+            h = self._block(l, h, pos)                   # ExDy: the encoding layers see every token
+        if n_early > 0:
+            self.pend_enc.append(h[0].copy())            # kept for the refill of the thinking layers
         for l in range(F, c.n_layers):
             h = self._block(l, h, pos)
-        self.trace.append([("late", [p])])
-        self.gen_layer_visits += n_late
+        self.trace.append(([("enc", [p])] if n_early > 0 else []) + [("late", [p])])
+        self.gen_layer_visits += n_early + n_late
         self.n_tok += 1
         return self._emit(h[0])
 
-    def _full_step(self, n_late: int) -> int:
+    def _full_step(self, n_late: int, n_early: int = 0) -> int:
         c = self.cfg
         F = c.n_layers - n_late
         p = self.n_tok
         self.tokens.append(self.last)
         pos = np.arange(self.n_front, p + 1)             # pending in-cycle tokens, then the newest
-        H = self.w["embed"][np.asarray(self.tokens[self.n_front:p + 1])]
-        for l in range(F):
-            H = self._block(l, H, pos)                   # refills front caches for the pending rows
+        if n_early > 0:
+            h_new = self.w["embed"][self.last][None, :]
+            for l in range(n_early):
+                h_new = self._block(l, h_new, np.array([p]))   # the pending tokens passed these layers in their own steps
+            H = np.concatenate([np.asarray(self.pend_enc, dtype=h_new.dtype).reshape(len(pos) - 1, h_new.shape[1]), h_new], 0)
+            base_new = h_new
+        else:
+            H = self.w["embed"][np.asarray(self.tokens[self.n_front:p + 1])]
+            base_new = H[-1:]
+        for l in range(n_early, F):
+            H = self._block(l, H, pos)                   # refills the thinking (and, without ExDy, all front) caches
         h = H[-1:]
         if c.full_pos_add_embed:
-            h = h + self.w["embed"][self.last][None, :]
+            h = h + base_new
         for l in range(F, c.n_layers):
             h = self._block(l, h, np.array([p]))         # only the newest row enters the late layers
         passes = []
-        if F > 0:
+        if n_early > 0:
+            passes.append(("enc", [p]))
+        if F - n_early > 0:
             passes.append(("front", [int(x) for x in pos]))
         passes.append(("late", [p]))
         self.trace.append(passes)
         self.gen_layer_visits += c.n_layers
-        self.refill_layer_visits += (len(pos) - 1) * F
+        self.refill_layer_visits += (len(pos) - 1) * (F - n_early)
+        self.pend_enc = []
         self.n_tok += 1
         self.n_front = self.n_tok
         return self._emit(h[0])
 
-    def decode_cycle(self, tau: int, n_late: int, max_new: int = 0, forced=None) -> list[int]:
+    def decode_cycle(self, tau: int, n_late: int, max_new: int = 0, forced=None, n_early: int = 0) -> list[int]:
         """Finish the open cycle, or run one whole cycle at a cycle boundary.
 
         Returns the argmax tokens of the steps run.  With ``forced`` (a sequence of
@@ -377,9 +411,14 @@ class DmtdOracle:
             raise RuntimeError("decode before prefill")
         if tau < 1 or not (1 <= n_late <= c.n_layers):
             raise ValueError("bad tau or n_late")
+        if not (0 <= n_early <= c.n_layers - n_late):
+            raise ValueError("n_early must lie in [0, L - n_late]")
         if self.n_late_in_use not in (None, n_late) and self.n_front != self.n_tok:
             raise RuntimeError("n_late changed while tokens await refill")
+        if self.n_early_in_use != n_early and self.n_front != self.n_tok:
+            raise RuntimeError("n_early changed while tokens await refill")
         self.n_late_in_use = n_late
+        self.n_early_in_use = n_early
         cap = max_new if max_new > 0 else 1 << 30
         out = []
 
@@ -388,7 +427,7 @@ class DmtdOracle:
                 raise OverflowError("sequence capacity")
             if forced is not None:
                 self.last = int(forced[len(out)])
-            tok = fn(n_late)
+            tok = fn(n_late, n_early)
             out.append(tok)
             self.n_emitted += 1
             self.last = tok

@@ -359,6 +359,128 @@ def test_layer_visit_counters_match_eq7_and_total_load(tau, n_late):
     assert total == consumed_after_prefill * L - (o.n_tok - o.n_front) * (L - n_late)
 
 
+# --------------------------------------------------------- ExDy variant (Sec. 2.1 / Sec. 3.3)
+
+SIX = di.ModelShape(6, 64, 4, 2, 16, 96, 50, dtype="fp32")
+
+
+def run_forced_exdy(cfg, w, toks, P, tau, n_late, n_early, n):
+    o = O.DmtdOracle(cfg, w, 96)
+    o.prefill(toks[:P], n_late, n_early)
+    while o.n_tok < n:
+        o.decode_cycle(tau, n_late, forced=toks[o.n_tok:o.n_tok + tau].tolist(), n_early=n_early)
+    return o
+
+
+@pytest.mark.parametrize("literal", [False, True])
+@pytest.mark.parametrize("tau,n_early,n_late", [(3, 1, 1), (3, 2, 2), (2, 1, 3), (4, 3, 1), (3, 0, 2), (1, 2, 2), (5, 2, 1)])
+def test_exdy_cycle_decode_equals_one_shot_masked_forward(tau, n_early, n_late, literal):
+    """The incremental machine with stored encoding outputs and thinking-layer refill == Eqs. 1-5 with h_enc
+    in place of h_emb (the last paragraph before Eq. 5), for both readings of Eq. 4."""
+    _, cfg, w = make(SIX, full_pos_add_embed=literal)
+    P, n = 5, 23
+    toks = di.make_prompts(SIX.vocab, 1, n + 8, seed=6)[0]
+    o = run_forced_exdy(cfg, w, toks, P, tau, n_late, n_early, n)
+    assert o.tokens == toks[:o.n_tok].tolist()
+    Z = np.stack(o.step_logits)
+    ref = O.masked_forward(toks[:o.n_tok], O.inference_mask(o.n_tok, P, tau), n_late, w, cfg, n_early=n_early)
+    assert np.abs(Z - ref[P - 1:P - 1 + len(Z)]).max() < 1e-11
+    # the variant changes the function unless nothing is skipped (the literal reading adds h_enc at full positions too)
+    plain = O.masked_forward(toks[:o.n_tok], O.inference_mask(o.n_tok, P, tau), n_late, w, cfg, n_early=0)
+    differs = np.abs(ref - plain).max() > 1e-6
+    assert differs == (n_early > 0 and (tau > 1 or literal))
+
+
+@pytest.mark.parametrize("tau", [2, 3, 5])
+@pytest.mark.parametrize("n_early", [1, 3, 5])
+def test_exdy_without_thinking_layers_is_ordinary_decoding(tau, n_early):
+    """x + y = L: every token passes every layer in its own step, nothing is left to refill, so any
+    cycle length reproduces the ordinary causal forward (default reading of Eq. 4)."""
+    _, cfg, w = make(SIX)
+    n_late = SIX.n_layers - n_early
+    P, n = 4, 18
+    toks = di.make_prompts(SIX.vocab, 1, n + 8, seed=7)[0]
+    o = run_forced_exdy(cfg, w, toks, P, tau, n_late, n_early, n)
+    van = O.vanilla_forward(toks[:o.n_tok], w, cfg)
+    Z = np.stack(o.step_logits)
+    assert np.abs(Z - van[P - 1:P - 1 + len(Z)]).max() < 1e-11
+    assert o.refill_layer_visits == 0
+    # and the caches equal those of one causal pass over the whole string
+    ref = O.DmtdOracle(cfg, w, 96)
+    ref.prefill(toks[:o.n_tok])
+    for l in range(SIX.n_layers):
+        assert np.abs(o.K[l][:o.n_tok] - ref.K[l][:o.n_tok]).max() < 1e-12
+        assert np.abs(o.V[l][:o.n_tok] - ref.V[l][:o.n_tok]).max() < 1e-12
+
+
+def test_exdy_n_early_zero_is_the_plain_method_bit_for_bit():
+    _, cfg, w = make(SIX)
+    toks = di.make_prompts(SIX.vocab, 1, 40, seed=8)[0]
+    a = run_forced_exdy(cfg, w, toks, 5, 3, 2, 0, 20)
+    b = run_forced(cfg, w, toks, 5, 3, 2, 20)
+    assert all(np.array_equal(x, y) for x, y in zip(a.step_logits, b.step_logits))
+    assert a.trace == b.trace and a.gen_layer_visits == b.gen_layer_visits
+
+
+def test_exdy_schedule_counters_and_refill_span():
+    """Layers per generated token follow Eq. 7 with L_d = x + y; the refill rows traverse only the thinking
+    layers; the total load stays that of ordinary decoding (Sec. 2.2)."""
+    _, cfg, w = make(SIX)
+    L, tau, x, y = SIX.n_layers, 3, 2, 1
+    o = O.DmtdOracle(cfg, w, 64)
+    o.prefill([3, 1, 4, 1, 5])
+    o.decode_cycle(tau, y, n_early=x)
+    g0, e0 = o.gen_layer_visits, o.n_emitted
+    for _ in range(4):
+        assert len(o.decode_cycle(tau, y, n_early=x)) == tau
+    assert (o.gen_layer_visits - g0) / ((o.n_emitted - e0) * L) == pytest.approx(O.plt_closed_form(L, y, tau, x), abs=1e-15)
+    assert O.plt_closed_form(L, y, tau, x) == pytest.approx((6 + 2 * 3) / 18)
+    consumed = o.n_tok - 5
+    assert o.gen_layer_visits + o.refill_layer_visits == consumed * L - (o.n_tok - o.n_front) * (L - x - y)
+    # a full pass of a later cycle: newest token through the encoding layers, 3 rows through the thinking layers,
+    # newest token through the decoding layers (Fig. 3 with the encoding block moved to the tokens' own passes)
+    full = [t for t in o.trace if any(g == "front" for g, _ in t)][-1]
+    p = full[-1][1][0]
+    assert full == [("enc", [p]), ("front", [p - 2, p - 1, p]), ("late", [p])]
+    late = o.trace[-1]
+    assert late == [("enc", [o.n_tok - 1]), ("late", [o.n_tok - 1])]
+
+
+def test_exdy_state_errors():
+    _, cfg, w = make(SIX)
+    o = O.DmtdOracle(cfg, w, 64)
+    o.prefill([1, 2, 3])
+    with pytest.raises(ValueError):
+        o.decode_cycle(3, 2, n_early=5)               # x + y > L
+    o.decode_cycle(3, 2, n_early=1)                   # leaves tokens awaiting refill
+    with pytest.raises(RuntimeError):
+        o.decode_cycle(3, 2, n_early=2)               # their stored encoding outputs belong to x = 1
+    o.decode_cycle(3, 2, max_new=1, n_early=1)        # the full step closes the gap
+    assert o.n_front == o.n_tok
+    o.decode_cycle(3, 2, n_early=2)
+
+
+def test_exdy_catches_planted_mistakes(monkeypatch):
+    """The masked-forward pin fails if the in-cycle tokens read the embedding instead of the encoding output,
+    or if the refill starts from the embeddings again."""
+    _, cfg, w = make(SIX)
+    toks = di.make_prompts(SIX.vocab, 1, 40, seed=9)[0]
+    P, tau, x, y = 5, 3, 2, 2
+    good = run_forced_exdy(cfg, w, toks, P, tau, y, x, 20)
+    ref = O.masked_forward(toks[:good.n_tok], O.inference_mask(good.n_tok, P, tau), y, w, cfg, n_early=x)
+    Zg = np.stack(good.step_logits)
+    assert np.abs(Zg - ref[P - 1:P - 1 + len(Zg)]).max() < 1e-11
+    orig = O.DmtdOracle._full_step
+
+    def refill_from_embeddings(self, n_late, n_early=0):
+        self.pend_enc = [self.w["embed"][t] for t in self.tokens[self.n_front:self.n_tok]]
+        return orig(self, n_late, n_early)
+    monkeypatch.setattr(O.DmtdOracle, "_full_step", refill_from_embeddings)
+    bad = run_forced_exdy(cfg, w, toks, P, tau, y, x, 20)
+    Zb = np.stack(bad.step_logits)
+    assert np.abs(Zb - ref[P - 1:P - 1 + len(Zb)]).max() > 1e-6
+
+
 def test_refill_row_by_row_equals_refill_as_one_batch():
     """Feeding the pending tokens through the front layers one at a time gives the same caches and logits."""
     _, cfg, w = make()
