@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(sh, n_late, ctx_full, ctx_late_list, batch):
+def algorithmic_bytes(sh, n_late, ctx_full, ctx_late_list, batch, n_early=0):
     """Bytes one decode cycle must move (each needed weight byte once per step, each live KV byte of a
     visited layer once per step); returns (cycle bytes, per-layer weight bytes, table bytes)."""
     e = sh.elem_bytes
@@ -31,7 +31,7 @@ def algorithmic_bytes(sh, n_late, ctx_full, ctx_late_list, batch):
     kv_tok = 2 * sh.n_kv_heads * hd * e * batch      # per layer per cached position
     total = sh.n_layers * per_layer + table + sh.n_layers * kv_tok * ctx_full
     for c in ctx_late_list:
-        total += n_late * per_layer + table + n_late * kv_tok * c
+        total += (n_early + n_late) * per_layer + table + (n_early + n_late) * kv_tok * c
     return total, per_layer, table
 
 
@@ -41,6 +41,10 @@ def main():
     ap.add_argument("--steps", type=int, default=160, help="timed decode cycles (tau tokens each)")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="C3")
+    ap.add_argument("--tau", type=int, default=0, help="override the workload's cycle length")
+    ap.add_argument("--n-late", type=int, default=0, help="override the workload's number of decoding layers")
+    ap.add_argument("--n-early", type=int, default=0, help="ExDy variant: encoding layers the in-cycle tokens reuse (0 = plain method)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
     ap.add_argument("--counters-run", action="store_true",
@@ -72,6 +76,8 @@ def main():
 
     wl = di.WORKLOADS[args.workload]
     sh, B, P, tau, n_late = wl.shape, wl.batch, wl.prompt_len, wl.tau, wl.n_late
+    tau, n_late, B = args.tau or tau, args.n_late or n_late, args.batch or B
+    n_early = args.n_early
     if args.counters_run:
         P = 64
     K, W = args.steps, args.warmup
@@ -82,6 +88,8 @@ def main():
     cfg = pkg.ModelConfig(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.intermediate, sh.vocab,
                           dtype=sh.dtype, max_batch=B, max_seq_len=max_seq, use_graphs=not args.no_graphs)
     eng = pkg.Engine(cfg, blob)
+    if n_early:
+        eng.set_n_early(n_early)
     t_setup = time.time() - t0
 
     def run(tau_run, cycles, warm):
@@ -111,7 +119,7 @@ def main():
     total_bytes = 0
     for c in range(K):
         base = ctx0 + c * tau
-        cyc, per_layer, table = algorithmic_bytes(sh, n_late, base + 1, [base + 1 + i for i in range(1, tau)], B)
+        cyc, per_layer, table = algorithmic_bytes(sh, n_late, base + 1, [base + 1 + i for i in range(1, tau)], B, n_early)
         total_bytes += cyc
     e2e_gbs = total_bytes / dt / 1e9
 
@@ -140,7 +148,8 @@ def main():
         "value": round(ntok / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if sh.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "tau": tau, "n_late": n_late, "batch": B, "prompt_len": P,
+        "config": {"workload": wl.name + ("" if (tau, n_late, B, n_early) == (wl.tau, wl.n_late, wl.batch, 0) else
+                                          f" [run with tau={tau}, n_late={n_late}, n_early={n_early}, batch={B}]"), "tau": tau, "n_late": n_late, "n_early": n_early, "batch": B, "prompt_len": P,
                    "context_at_start": ctx0, "graphs": not args.no_graphs},
         "tau1_tokens_per_s": round(ntok1 / dt1, 2), "speedup_vs_tau1": round((ntok / dt) / (ntok1 / dt1), 4),
         "end_to_end": {"algorithmic_GB_per_cycle": round(total_bytes / K / 1e9, 4), "achieved_GBs": round(e2e_gbs, 1),

@@ -127,7 +127,7 @@ int dmtd_get_state(const dmtd_ctx* ctx, int32_t* n_tok, int32_t* n_front, int32_
                    int64_t* counters);
 
 /* Schedule trace since the last reset: one record of 4 int32 per (pass, layer group):
- * pass number (1 = prefill), group (0 = front layers, 1 = late layers), first
+ * pass number (1 = prefill), group (0 = front layers; with n_early > 0: the thinking layers, 1 = late layers, 2 = encoding layers of the ExDy variant), first
  * position, number of consecutive positions.  buf: HOST, cap_records records.
  * n_records receives the total number available (which may exceed cap_records). */
 int dmtd_get_trace(const dmtd_ctx* ctx, int32_t* buf, int32_t cap_records, int32_t* n_records);
@@ -150,6 +150,16 @@ int dmtd_read_kv(dmtd_ctx* ctx, int32_t layer, int32_t b, int32_t n_pos, float* 
 #define DMTD_K_LMHEAD  4   /* final RMSNorm + LM head (Eq. 5) + argmax partials */
 #define DMTD_K_ATTN    5   /* split-K GQA decode attention over the current context */
 int dmtd_time_kernel(dmtd_ctx* ctx, int32_t kind, int32_t rows, int32_t reps, float* avg_us);
+
+/* ExDy variant (Sec. 2.1, the paragraph before Eq. 5; layer allocations of Sec. 3.3): the in-cycle tokens
+ * reuse the first n_early (encoding) layers as well as the last n_late (decoding) layers, i.e. h_masked is built
+ * from h_enc instead of h_emb.  A late-only step then runs layers [0, n_early) and [L - n_late, L) on its token
+ * and keeps the encoding output; the next full step refills only the thinking layers [n_early, L - n_late) from
+ * the stored outputs.  n_early = 0 (the default) is the plain method; the setting survives dmtd_reset.
+ * Allowed before prefill or whenever no token awaits refill (under the literal Eq. 4 reading only before prefill).
+ * dmtd_decode_cycle then requires n_early + n_late <= n_layers (DMTD_EINVAL).
+ * Errors: DMTD_EINVAL (n_early outside [0, n_layers - 1]), DMTD_ESTATE. */
+int dmtd_set_n_early(dmtd_ctx* ctx, int32_t n_early);
 
 /* Back to the state right after dmtd_create (caches are treated as empty). */
 int dmtd_reset(dmtd_ctx* ctx);

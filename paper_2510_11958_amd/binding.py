@@ -67,6 +67,8 @@ def load_library():
     lib.dmtd_read_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float), C.c_size_t]
     lib.dmtd_time_kernel.restype = C.c_int
     lib.dmtd_time_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
+    lib.dmtd_set_n_early.restype = C.c_int
+    lib.dmtd_set_n_early.argtypes = [C.c_void_p, C.c_int32]
     lib.dmtd_reset.restype = C.c_int
     lib.dmtd_reset.argtypes = [C.c_void_p]
     lib.dmtd_destroy.restype = None
@@ -200,7 +202,8 @@ class Engine:
         self._check(self.lib.dmtd_get_trace(self._h, None, 0, C.byref(n)))
         buf = np.empty((max(n.value, 1), 4), np.int32)
         self._check(self.lib.dmtd_get_trace(self._h, _i32p(buf), n.value, C.byref(n)))
-        return [(int(p), "front" if g == 0 else "late", list(range(int(f), int(f) + int(c)))) for p, g, f, c in buf[:n.value]]
+        names = {0: "front", 1: "late", 2: "enc"}
+        return [(int(p), names[int(g)], list(range(int(f), int(f) + int(c)))) for p, g, f, c in buf[:n.value]]
 
     def read_kv(self, layer: int, b: int, n_pos: int) -> np.ndarray:
         out = np.empty((2, self.cfg.n_kv_heads, n_pos, self.cfg.head_dim), np.float32)
@@ -214,6 +217,10 @@ class Engine:
         us = C.c_float()
         self._check(self.lib.dmtd_time_kernel(self._h, self.KERNEL_KINDS[kind], rows, reps, C.byref(us)))
         return us.value
+
+    def set_n_early(self, n_early: int):
+        """ExDy variant: in-cycle tokens also pass the first ``n_early`` layers (0 = plain method)."""
+        self._check(self.lib.dmtd_set_n_early(self._h, int(n_early)))
 
     def reset(self):
         self._check(self.lib.dmtd_reset(self._h))

@@ -52,6 +52,7 @@ struct Ws {   // device workspace carve-up (byte offsets)
   size_t tokens, emitted, forced, state, inv_freq, rope_tab;
   size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
   size_t gemm_part;                            // K-split partial sums of the tiled kernel
+  size_t pend_enc, enc_tmp;                    // ExDy: stored encoding outputs of pending tokens; of a prefill chunk
   size_t total;
 };
 
@@ -152,6 +153,8 @@ Ws layout(const dmtd_config& c) {
   w.forced = take((size_t)kMaxTau * B * 4);
   w.state = take(256);
   w.inv_freq = take((hd / 2) * 8);
+  w.pend_enc = take(B * kMaxTau * d * 4);
+  w.enc_tmp = take(rows * d * 4);
   w.rope_tab = take(S * (hd / 2) * 8);                 // (cos, sin) per position and frequency
   if (c.dtype == DMTD_DTYPE_BF16) {
     const size_t parts = (d + 15) / 16;
@@ -468,11 +471,11 @@ hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int ad
   if (c->packed) {
     hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden, add_embed,
                        (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset,
-                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp);
+                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp, (const float*)nullptr);
     dst.n_parts = 1;
   } else {
     hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden,
-                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset);
+                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, (const float*)nullptr);
   }
   return hipGetLastError();
 }
@@ -580,24 +583,87 @@ Rows late_rows(dmtd_ctx* c) {
 // One decode step (Sec. 2.2).  Full: embed the pending rows and the newest row, run the front
 // layers on all of them, keep the newest row, run the late layers on it.  Late: embed the
 // newest token and run the late layers only (Eq. 4, m = 0).
+// ExDy row moves (rows_op_kernel): with or without the packed input of the norm of layer next_layer
+hipError_t rows_op(dmtd_ctx* c, int mode, int n_rows, float* dst, const float* src_a, const float* src_b, int r, int c0, int rc,
+                   int next_layer, bf16_t* xb, bf16_t* xb_lo, float* ssp) {
+  const dmtd_config& cf = c->cfg;
+  if (c->packed)
+    hipLaunchKernelGGL(rows_op_kernel<true>, dim3(n_rows), dim3(256), 0, c->stream, mode, dst, src_a, src_b, cf.hidden, kMaxTau, r, c0, rc,
+                       dev_state(c), (const bf16_t*)norm_gain_for_layer(c, next_layer), xb, xb_lo, ssp);
+  else
+    hipLaunchKernelGGL(rows_op_kernel<false>, dim3(n_rows), dim3(256), 0, c->stream, mode, dst, src_a, src_b, cf.hidden, kMaxTau, r, c0, rc,
+                       dev_state(c), (const bf16_t*)nullptr, (bf16_t*)nullptr, (bf16_t*)nullptr, (float*)nullptr);
+  return hipGetLastError();
+}
+
+// One decode step (Sec. 2.2).  Full: embed the pending rows and the newest row, run the front
+// layers on all of them, keep the newest row, run the late layers on it.  Late: embed the
+// newest token and run the late layers only (Eq. 4, m = 0).
+// ExDy variant (n_early = E > 0): every step first runs its own token through the E encoding layers; a late
+// step stores that output for the refill and jumps to the late layers; a full step gathers the stored outputs
+// of the pending tokens and the newest token's, runs the thinking layers E .. F-1 on them, and goes on as before.
 hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
   const dmtd_config& cf = c->cfg;
-  const int F = cf.n_layers - n_late;
+  const int F = cf.n_layers - n_late, E = c->sched.n_early;
   Rows front = front_rows(c), late = late_rows(c);
+  float* pend = (float*)(c->ws + c->o.pend_enc);
   hipError_t e;
+  if (E > 0) {
+    if ((e = embed_rows(c, late, POS_NTOK, 0, 1, 0)) != hipSuccess) return e;
+    for (int l = 0; l < E; ++l)
+      if ((e = run_layer(c, l, late, 1, POS_NTOK, 0)) != hipSuccess) return e;
+  }
   if (full) {
     // the pending rows are causal among themselves, so groups of rows may pass the front
     // layers one after another (each group streams those layers' weights once)
     int c0 = 0, rc = 0;
-    for (; c0 < r; c0 += rc) {
-      rc = r - c0 < kMaxRows ? r - c0 : kMaxRows;
-      if ((e = embed_rows(c, front, POS_NFRONT, c0, rc, 0)) != hipSuccess) return e;
-      for (int l = 0; l < F; ++l)
-        if ((e = run_layer(c, l, front, rc, POS_NFRONT, c0)) != hipSuccess) return e;
+    if (F > E) {
+      for (; c0 < r; c0 += rc) {
+        rc = r - c0 < kMaxRows ? r - c0 : kMaxRows;
+        if (E > 0) {
+          if ((e = rows_op(c, ROWS_GATHER, c->batch * rc, front.h, pend, late.h, r, c0, rc, E, front.xb, front.xb_lo, front.ssp)) != hipSuccess) return e;
+          front.n_parts = 1;
+        } else {
+          if ((e = embed_rows(c, front, POS_NFRONT, c0, rc, 0)) != hipSuccess) return e;
+        }
+        for (int l = E; l < F; ++l)
+          if ((e = run_layer(c, l, front, rc, POS_NFRONT, c0)) != hipSuccess) return e;
+      }
+      if (E > 0) {
+        // the newest row continues; the literal Eq. 4 reading adds its encoding output (still in the late row buffer)
+        if (c->packed)
+          hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden, 0,
+                             (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
+                             (const bf16_t*)norm_gain_for_layer(c, F), late.xb, late.xb_lo, late.ssp,
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr);
+        else
+          hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden,
+                             0, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        late.n_parts = 1;
+      } else {
+        if ((e = take_last_rows(c, front, late, rc, cf.full_pos_add_embed ? 1 : 0, POS_NFRONT, c0 - rc, F)) != hipSuccess) return e;
+      }
+    } else if (E > 0 && cf.full_pos_add_embed) {
+      // no thinking layers: h_think = h_enc, and the literal reading feeds their sum
+      if ((e = rows_op(c, ROWS_ADD, c->batch, late.h, late.h, late.h, 1, 0, 1, F, late.xb, late.xb_lo, late.ssp)) != hipSuccess) return e;
+      late.n_parts = 1;
+    } else if (E == 0) {
+      // n_late = all layers: the newest token's embedding enters the late layers directly
+      if ((e = embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
+      if (cf.full_pos_add_embed && (e = add_embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
     }
-    if ((e = take_last_rows(c, front, late, rc, cf.full_pos_add_embed ? 1 : 0, POS_NFRONT, c0 - rc, F)) != hipSuccess) return e;
   } else {
-    if ((e = embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
+    if (E > 0) {
+      // keep the encoding output for the refill; the row itself jumps to the late layers
+      if (F > E) {
+        if ((e = rows_op(c, ROWS_STASH, c->batch, pend, late.h, nullptr, 1, 0, 1, F, late.xb, late.xb_lo, late.ssp)) != hipSuccess) return e;
+        late.n_parts = 1;
+      }
+    } else {
+      if ((e = embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
+    }
   }
   for (int l = F; l < cf.n_layers; ++l)
     if ((e = run_layer(c, l, late, 1, POS_NTOK, 0)) != hipSuccess) return e;
@@ -621,7 +687,7 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
     HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late, c->att_bucket * 2 + (c->share_kv ? 1 : 0));
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late * 4096 + c->sched.n_early, c->att_bucket * 2 + (c->share_kv ? 1 : 0));
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -655,8 +721,18 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
     const int r = P - p0 < kPrefillChunk ? P - p0 : kPrefillChunk;
     choose_attention(c, p0 + r);
     if ((e = embed_rows(c, front, POS_EXPLICIT, p0, r, 0)) != hipSuccess) return e;
+    const int E = c->sched.n_early;
     for (int l = 0; l < cf.n_layers; ++l) {
-      if (l == add_at && (e = add_embed_rows(c, front, POS_EXPLICIT, p0, r, l)) != hipSuccess) return e;
+      if (add_at >= 0 && E > 0 && l == E) {
+        // literal Eq. 4, ExDy variant: the encoding output is what full positions get added at the late boundary
+        if ((e = hipMemcpyAsync(c->ws + c->o.enc_tmp, front.h, (size_t)c->batch * r * cf.hidden * 4, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess) return e;
+      }
+      if (l == add_at) {
+        if (E > 0) {
+          if ((e = rows_op(c, ROWS_ADD, c->batch * r, front.h, front.h, (const float*)(c->ws + c->o.enc_tmp), 1, 0, 1, l, front.xb, front.xb_lo, front.ssp)) != hipSuccess) return e;
+          front.n_parts = 1;
+        } else if ((e = add_embed_rows(c, front, POS_EXPLICIT, p0, r, l)) != hipSuccess) return e;
+      }
       if ((e = run_layer(c, l, front, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
     }
     r_last = r; p_last = p0;
@@ -848,6 +924,7 @@ int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prom
   if (batch < 1 || batch > cf.max_batch) { c->err = "batch outside [1, max_batch]"; return DMTD_EINVAL; }
   if (prompt_len < 1) { c->err = "prompt_len must be >= 1"; return DMTD_EINVAL; }
   if (cf.full_pos_add_embed && (n_late < 1 || n_late > cf.n_layers)) { c->err = "the literal Eq. 4 reading needs n_late at prefill"; return DMTD_EINVAL; }
+  if (cf.full_pos_add_embed && c->sched.n_early + n_late > cf.n_layers) { c->err = "n_early + n_late exceeds the number of layers"; return DMTD_EINVAL; }
   if (c->sched.n_tok != 0) { c->err = "already prefilled; call dmtd_reset first"; return DMTD_ESTATE; }
   if (prompt_len >= cf.max_seq_len) { c->err = "prompt does not leave room for a generated token"; return DMTD_ECAPACITY; }
   for (size_t i = 0; i < (size_t)batch * prompt_len; ++i)
@@ -1039,6 +1116,17 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
   (void)hipEventDestroy(e1);
   if (e != hipSuccess) { c->err = std::string("dmtd_time_kernel: ") + hipGetErrorString(e); return DMTD_EHIP; }
   *avg_us = ms * 1000.0f / (float)launches;
+  return DMTD_OK;
+}
+
+int dmtd_set_n_early(dmtd_ctx* c, int32_t n_early) {
+  if (!c) return DMTD_EINVAL;
+  if (n_early < 0 || n_early >= c->cfg.n_layers) { c->err = "n_early must be in [0, n_layers - 1]"; return DMTD_EINVAL; }
+  if (c->sched.n_tok != c->sched.n_front) { c->err = "n_early changed while tokens await refill"; return DMTD_ESTATE; }
+  if (c->sched.n_tok != 0 && c->cfg.full_pos_add_embed && n_early != c->sched.n_early) {
+    c->err = "under the literal Eq. 4 reading n_early is fixed at prefill"; return DMTD_ESTATE;
+  }
+  c->sched.n_early = n_early;
   return DMTD_OK;
 }
 

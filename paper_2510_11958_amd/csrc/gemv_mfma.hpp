@@ -330,15 +330,16 @@ __global__ void __launch_bounds__(256) embed_pack_kernel(
 }
 
 __global__ void __launch_bounds__(256) take_last_pack_kernel(
-    const float* __restrict__ src, float* __restrict__ dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
+    const float* __restrict__ src, float* dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
     const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset, const bf16_t* __restrict__ gain,
-    bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp) {
+    bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp, const float* add_rows /* nullable; may be dst */) {
   const int b = blockIdx.x;
   const float* s = src + ((size_t)b * r + (r - 1)) * d;
   float* o = dst + (size_t)b * d;
   const bf16_t* e = nullptr;
   if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + r - 1] * d;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? bf16_to_f32(e[k]) : 0.0f);
+  const float* ar = add_rows ? add_rows + (size_t)b * d : nullptr;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? bf16_to_f32(e[k]) : 0.0f) + (ar ? ar[k] : 0.0f);
   pack_row_for_norm(o, gain, d, xb + (size_t)b * d, xb_lo + (size_t)b * d, ssp + b);
 }
 
@@ -351,6 +352,49 @@ __global__ void __launch_bounds__(256) add_embed_pack_kernel(
   float* o = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += bf16_to_f32(e[k]);
   pack_row_for_norm(o, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);
+}
+
+// ---- ExDy variant (Sec. 2.1, last paragraph before Eq. 5): tokens inside a cycle pass the first
+// ---- (encoding) layers in their own step; their encoding outputs wait in a per-sequence store
+// ---- until the next full step refills the thinking layers from them.
+
+// dst[row] = src_a[row_a] (+ src_b[row_b]); optionally the packed input of the next norm.
+// One block per destination row.  Row selection, per mode:
+//   ROWS_STASH   dst = store[b][n_tok - n_front] (the slot of the newest pending token), src_a = rows[b];
+//                the pack (if any) is of the SOURCE row, into xb[b] (the row goes on to the decoding layers)
+//   ROWS_GATHER  launch rows c0 .. c0 + rc - 1 of the r rows of a full step: row i < r - 1 comes from
+//                store[b][i], row r - 1 (the newest token) from src_b[b]; dst = rows[b * rc + (i - c0)]
+//   ROWS_ADD     dst[row] = src_a[row] + src_b[row], in place allowed
+enum RowsMode : int { ROWS_STASH = 0, ROWS_GATHER = 1, ROWS_ADD = 2 };
+
+template <bool PACK>
+__global__ void __launch_bounds__(256) rows_op_kernel(int mode, float* __restrict__ dst, const float* src_a, const float* src_b,
+                                                      int d, int store_rows /* slots per sequence */, int r, int c0, int rc,
+                                                      const DevState* st, const bf16_t* __restrict__ gain,
+                                                      bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp) {
+  const int row = blockIdx.x;
+  const float* a = nullptr;
+  const float* bsrc = nullptr;
+  float* o = nullptr;
+  int pack_row = row;
+  if (mode == ROWS_STASH) {
+    const int slot = st->n_tok - st->n_front;
+    a = src_a + (size_t)row * d;
+    o = dst + ((size_t)row * store_rows + slot) * d;
+  } else if (mode == ROWS_GATHER) {
+    const int b = row / rc, i = c0 + row % rc;
+    a = i < r - 1 ? src_a + ((size_t)b * store_rows + i) * d : src_b + (size_t)b * d;
+    o = dst + (size_t)row * d;
+  } else {
+    a = src_a + (size_t)row * d;
+    bsrc = src_b + (size_t)row * d;
+    o = dst + (size_t)row * d;
+  }
+  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = a[k] + (bsrc ? bsrc[k] : 0.f);
+  if (PACK) {
+    __syncthreads();
+    pack_row_for_norm(mode == ROWS_STASH ? a : o, gain, d, xb + (size_t)pack_row * d, xb_lo + (size_t)pack_row * d, ssp + pack_row);
+  }
 }
 
 }  // namespace dmtd

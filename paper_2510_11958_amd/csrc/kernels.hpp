@@ -168,12 +168,13 @@ __global__ void embed_kernel(const WT* __restrict__ table, const int* __restrict
   for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = Elem<WT>::to_f32(src[k]);
 }
 
-// dst[b] = src[b*r + r-1] (+ table[token of that row] under the literal Eq. 4 reading):
-// only each sequence's newest row continues into the late layers (Sec. 2.2).
+// dst[b] = src[b*r + r-1] (+ table[token of that row] under the literal Eq. 4 reading; ExDy variant of that
+// reading: + add_rows[b], the row's encoding output, which may be dst itself): only each sequence's newest
+// row continues into the late layers (Sec. 2.2).
 template <typename WT>
-__global__ void take_last_rows_kernel(const float* __restrict__ src, float* __restrict__ dst, int r, int d,
+__global__ void take_last_rows_kernel(const float* __restrict__ src, float* dst, int r, int d,
                                       int add_embed, const WT* __restrict__ table, const int* __restrict__ tokens,
-                                      int s_max, const DevState* st, int sel, int explicit_pos) {
+                                      int s_max, const DevState* st, int sel, int explicit_pos, const float* add_rows) {
   const int b = blockIdx.x;
   const float* s = src + ((size_t)b * r + (r - 1)) * d;
   float* o = dst + (size_t)b * d;
@@ -182,7 +183,8 @@ __global__ void take_last_rows_kernel(const float* __restrict__ src, float* __re
     const int pos = row_base(st, sel, explicit_pos) + r - 1;
     e = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   }
-  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? Elem<WT>::to_f32(e[k]) : 0.0f);
+  const float* ar = add_rows ? add_rows + (size_t)b * d : nullptr;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? Elem<WT>::to_f32(e[k]) : 0.0f) + (ar ? ar[k] : 0.0f);
 }
 
 // rows[row] += table[token at the row's position]   (literal Eq. 4 during prefill)

@@ -23,12 +23,13 @@ struct Sched {
   int n_front = 0;    // tokens that have entered the front layers' caches
   int phase = 0;      // tokens of the current cycle already emitted (prefill's token counts for cycle 1)
   int n_late_in_use = 0;
+  int n_early = 0;    // ExDy variant: encoding layers the in-cycle tokens pass in their own step (0 = plain method)
   int pass_no = 0;
   int64_t gen_layer_visits = 0, refill_layer_visits = 0, n_emitted = 0, n_full_steps = 0;
-  std::vector<int32_t> trace;   // records of 4: pass, group (0 front / 1 late), first position, count
+  std::vector<int32_t> trace;   // records of 4: pass, group (0 front or thinking / 1 late / 2 encoding), first position, count
 
   void reset() {
-    n_tok = n_front = phase = n_late_in_use = pass_no = 0;
+    n_tok = n_front = phase = n_late_in_use = pass_no = 0;   // n_early is a setting: it survives a reset
     gen_layer_visits = refill_layer_visits = n_emitted = n_full_steps = 0;
     trace.clear();
   }
@@ -53,6 +54,7 @@ struct Sched {
     if (n_tok == 0) { err = 2; why = "decode before prefill"; return false; }
     if (tau < 1) { err = 1; why = "tau must be >= 1"; return false; }
     if (n_late < 1 || n_late > n_layers) { err = 1; why = "n_late must be in [1, n_layers]"; return false; }
+    if (n_early + n_late > n_layers) { err = 1; why = "n_early + n_late exceeds the number of layers"; return false; }
     if (n_late_in_use != 0 && n_late_in_use != n_late && n_front != n_tok) {
       err = 2; why = "n_late changed while tokens await refill"; return false;
     }
@@ -76,16 +78,17 @@ struct Sched {
     const int F = n_layers - n_late;
     for (const Step& s : steps) {
       pass_no += 1;
+      if (n_early > 0) record(2, s.pos, 1);          // the step's own token through the encoding layers
       if (s.full) {
-        if (F > 0) record(0, n_front, s.rows);
+        if (F - n_early > 0) record(0, n_front, s.rows);
         record(1, s.pos, 1);
         gen_layer_visits += n_layers;
-        refill_layer_visits += (int64_t)(s.rows - 1) * F;
+        refill_layer_visits += (int64_t)(s.rows - 1) * (F - n_early);
         n_tok += 1; n_front = n_tok; phase = 1;
         n_full_steps += 1;
       } else {
         record(1, s.pos, 1);
-        gen_layer_visits += n_late;
+        gen_layer_visits += n_early + n_late;
         n_tok += 1; phase += 1;
       }
       n_emitted += 1;

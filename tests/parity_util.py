@@ -34,13 +34,15 @@ class Pair:
     """The engine and one oracle per sequence, advanced in lockstep with teacher forcing."""
 
     def __init__(self, sh, blob, max_seq_len, batch=1, literal=False, use_graphs=True, oracle_dtype=np.float64,
-                 weights_dev=None):
-        self.sh, self.batch = sh, batch
+                 weights_dev=None, n_early=0):
+        self.sh, self.batch, self.n_early = sh, batch, n_early
         self.eng = pkg.Engine(engine_config(sh, max_seq_len, batch, full_pos_add_embed=literal, use_graphs=use_graphs),
                               blob if weights_dev is None else weights_dev)
         ocfg = oracle_config(sh, full_pos_add_embed=literal)
         w = O.unpack_weights(blob, ocfg, oracle_dtype)
         self.orcs = [O.DmtdOracle(ocfg, w, max_seq_len, oracle_dtype) for _ in range(batch)]
+        if n_early:
+            self.eng.set_n_early(n_early)
         self.worst = 0.0
         self.token_checks = 0
         self.token_skips = 0
@@ -60,7 +62,7 @@ class Pair:
     def prefill(self, prompts, n_late=0):
         first = self.eng.prefill(prompts, n_late)
         for b, o in enumerate(self.orcs):
-            o.prefill(prompts[b], n_late if n_late else None)
+            o.prefill(prompts[b], n_late if n_late else None, self.n_early)
         self._compare(first)
         return first
 
@@ -70,7 +72,7 @@ class Pair:
         f = np.stack([tokens_by_pos[b][nt:nt + 1] for b in range(self.batch)])
         out = self.eng.decode_cycle(tau, n_late, max_new=1, forced=f)
         for b, o in enumerate(self.orcs):
-            o.decode_cycle(tau, n_late, max_new=1, forced=f[b].tolist())
+            o.decode_cycle(tau, n_late, max_new=1, forced=f[b].tolist(), n_early=self.n_early)
         assert out.shape == (self.batch, 1)
         self._compare(out[:, 0])
         s = self.eng.state()
@@ -80,10 +82,11 @@ class Pair:
     def compare_kv(self, atol_rel):
         n = self.orcs[0].n_tok
         for l in range(self.sh.n_layers):
-            # front layers hold positions < n_front, late layers < n_tok
+            # front (ExDy: thinking) layers hold positions < n_front, late layers and ExDy's encoding layers < n_tok
             for b, o in enumerate(self.orcs):
                 kv = self.eng.read_kv(l, b, n)
-                upto = o.n_tok if l >= self.sh.n_layers - (o.n_late_in_use or self.sh.n_layers) else o.n_front
+                late = l >= self.sh.n_layers - (o.n_late_in_use or self.sh.n_layers)
+                upto = o.n_tok if (late or l < self.n_early) else o.n_front
                 for which, ref in ((0, o.K[l]), (1, o.V[l])):
                     r = np.transpose(ref[:upto], (1, 0, 2))
                     err = np.abs(kv[which][:, :upto] - r).max() / max(np.abs(r).max(), 1e-30)

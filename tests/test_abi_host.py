@@ -91,6 +91,56 @@ def test_layer_visit_counters_give_eq7(L, n_late, tau):
     assert total == consumed * L - (s1["n_tok"] - s1["n_front"]) * (L - n_late)
 
 
+@pytest.mark.parametrize("tau,n_early,n_late", [(3, 2, 1), (4, 1, 2), (2, 3, 3), (3, 0, 2), (5, 2, 2)])
+def test_exdy_schedule_matches_the_oracle_machine(tau, n_early, n_late):
+    """ExDy variant: the library's scheduler (dry run) and the oracle's cycle machine visit the same
+    (pass, layer group, positions), count the same layer visits, and give Eq. 7 with L_d = x + y."""
+    import dmtd_inputs as di
+    from oracle import dmtd_oracle as O
+    L = 6
+    sh = di.ModelShape(L, 64, 4, 2, 16, 96, 50, dtype="fp32")
+    ocfg = O.OracleConfig(L, 64, 4, 2, 16, 96, 50)
+    orc = O.DmtdOracle(ocfg, O.unpack_weights(di.make_weight_blob(sh, seed=1, std=0.1), ocfg), 64)
+    e = dry(n_layers=L)
+    e.set_n_early(n_early)
+    e.prefill([[1, 2, 3, 4]])
+    orc.prefill([1, 2, 3, 4], n_early=n_early)
+    for _ in range(4):
+        n = e.decode_cycle(tau, n_late).shape[1]
+        assert len(orc.decode_cycle(tau, n_late, n_early=n_early)) == n
+    want = [(i + 1, g, pos) for i, passes in enumerate(orc.trace) for g, pos in passes]
+    got = e.trace()
+    order = {"enc": 0, "front": 1, "late": 2}
+    assert sorted(got, key=lambda t: (t[0], order[t[1]])) == sorted(want, key=lambda t: (t[0], order[t[1]]))
+    s = e.state()
+    assert (s["n_tok"], s["n_front"], s["gen_layer_visits"], s["refill_layer_visits"]) == \
+        (orc.n_tok, orc.n_front, orc.gen_layer_visits, orc.refill_layer_visits)
+
+
+def test_exdy_setting_errors():
+    e = dry(n_layers=6)
+    with pytest.raises(pkg.DmtdError) as ei:
+        e.set_n_early(6)
+    assert ei.value.code == pkg.binding.DMTD_EINVAL
+    with pytest.raises(pkg.DmtdError):
+        e.set_n_early(-1)
+    e.set_n_early(2)
+    e.prefill([[1, 2, 3]])
+    with pytest.raises(pkg.DmtdError) as ei:
+        e.decode_cycle(3, 5)                      # 2 + 5 > 6
+    assert ei.value.code == pkg.binding.DMTD_EINVAL and e.state()["n_tok"] == 3
+    e.decode_cycle(3, 2)                          # two late steps: tokens await refill
+    with pytest.raises(pkg.DmtdError) as ei:
+        e.set_n_early(1)
+    assert ei.value.code == pkg.binding.DMTD_ESTATE
+    e.decode_cycle(3, 2, max_new=1)               # the full step refills them
+    e.set_n_early(1)
+    e.reset()
+    e.prefill([[1, 2, 3]])
+    e.decode_cycle(2, 4)
+    assert ("enc", [3]) in [(g, p) for _, g, p in e.trace()]      # the setting survived the reset
+
+
 def test_state_and_argument_errors_leave_state_unchanged():
     e = dry(max_seq_len=8)
     with pytest.raises(pkg.DmtdError) as ex:

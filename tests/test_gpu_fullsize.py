@@ -147,6 +147,40 @@ def test_c4_c5_batched_short_prompt(model_4b, name, prompt_len):
     print(f"{name} (B={B}, P={prompt_len}): worst {worst:.2e}")
 
 
+@pytest.mark.parametrize("n_early,n_late", [(4, 4), (8, 8)])
+def test_exdy_at_4b_shapes(model_4b, n_early, n_late):
+    """ExDy allocations of Sec. 3.3 (E4D4, E8D8) at the 4B shape, tau = 3, batch 2, shortened prompt: prefill
+    and the first three cycles teacher-forced against standalone float32 oracle runs of both sequences."""
+    sh, blob, ocfg, w32, dev = model_4b
+    B, P, tau = 2, 72, 3
+    prompts = di.make_prompts(sh.vocab, B, P, seed=21)
+    toks = forced_string(sh.vocab, B, prompts, P + 24)
+    eng = pkg.Engine(engine_config(sh, P + 24, B), dev)
+    eng.set_n_early(n_early)
+    first = eng.prefill(prompts)
+    orcs = [O.DmtdOracle(ocfg, w32, P + 24, np.float32) for _ in range(B)]
+    worst = 0.0
+    for b in range(B):
+        orcs[b].prefill(prompts[b], n_early=n_early)
+        worst, ref = _check_against_oracle(eng, orcs[b], b, worst)
+        if top2_margin(ref) > MARGIN:
+            assert int(first[b]) == int(np.argmax(ref))
+    for _ in range((tau - 1) + 2 * tau):
+        nt = eng.state()["n_tok"]
+        f = np.stack([toks[b][nt:nt + 1] for b in range(B)])
+        out = eng.decode_cycle(tau, n_late, max_new=1, forced=f)
+        for b in range(B):
+            orcs[b].decode_cycle(tau, n_late, max_new=1, forced=f[b].tolist(), n_early=n_early)
+            worst, ref = _check_against_oracle(eng, orcs[b], b, worst)
+            if top2_margin(ref) > MARGIN:
+                assert int(out[b, 0]) == int(np.argmax(ref))
+        s = eng.state()
+        assert (s["n_tok"], s["n_front"], s["gen_layer_visits"], s["refill_layer_visits"]) == \
+            (orcs[0].n_tok, orcs[0].n_front, orcs[0].gen_layer_visits, orcs[0].refill_layer_visits)
+    assert worst < TOL_BF16, worst
+    print(f"E{n_early}D{n_late}: worst {worst:.2e}")
+
+
 def test_batch_rows_are_independent_and_identical_prompts_agree(model_4b):
     """Property at any size: a sequence's outputs do not depend on its neighbours in the batch."""
     sh, blob, ocfg, w32, dev = model_4b

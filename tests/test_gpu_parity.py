@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import dmtd_inputs as di
+import paper_2510_11958_amd as pkg
 from parity_util import Pair
 
 pytestmark = pytest.mark.gpu
@@ -84,6 +85,61 @@ def test_small_shapes_teacher_forced(name, literal):
     assert p.worst < tol, p.worst
     p.compare_kv(1e-5 if sh.dtype == "fp32" else 2e-2)
     print(f"{name} literal={literal}: worst {p.worst:.2e}, tokens checked {p.token_checks}, skipped {p.token_skips}")
+
+
+EXDY = {
+    # name: (shape, batch, prompt_len, steps, tau, n_early, n_late)
+    "f32_e2d2": (di.ModelShape(6, 64, 4, 2, 64, 96, 61, dtype="fp32"), 2, 6, 14, 3, 2, 2),
+    "f32_e1d1_tau5": (di.ModelShape(5, 72, 2, 2, 64, 104, 93, dtype="fp32"), 1, 7, 16, 5, 1, 1),
+    "f32_no_thinking": (di.ModelShape(4, 64, 4, 2, 64, 96, 50, dtype="fp32"), 1, 5, 9, 3, 1, 3),
+    "bf16_e1d2": (di.ModelShape(6, 256, 8, 2, 128, 512, 1000, dtype="bf16"), 1, 200, 12, 3, 1, 2),
+    "bf16_e2d2_batch2": (di.ModelShape(6, 128, 4, 2, 64, 256, 515, dtype="bf16"), 2, 130, 10, 4, 2, 2),
+}
+
+
+@pytest.mark.parametrize("literal", [False, True])
+@pytest.mark.parametrize("name", list(EXDY))
+def test_exdy_teacher_forced(name, literal):
+    """ExDy variant (in-cycle tokens reuse the first n_early layers; the refill covers the thinking layers only):
+    every step's logits and, at the end, all caches against the oracle."""
+    sh, batch, P, steps, tau, n_early, n_late = EXDY[name]
+    blob = di.make_weight_blob(sh, seed=11, std=0.05 if sh.dtype == "fp32" else 0.03, gain_sigma=0.2)
+    prompts = di.make_prompts(sh.vocab, batch, P, seed=4)
+    toks = forced_string(sh.vocab, batch, prompts, P + steps + 2)
+    p = Pair(sh, blob, P + steps + 8, batch=batch, literal=literal, n_early=n_early)
+    p.prefill(prompts, n_late if literal else 0)
+    for _ in range(steps):
+        p.step_forced(tau, n_late, toks)
+    tol = TOL_F32 if sh.dtype == "fp32" else TOL_BF16
+    assert p.worst < tol, p.worst
+    p.compare_kv(1e-5 if sh.dtype == "fp32" else 2e-2)
+    got = p.eng.state()
+    o = p.orcs[0]
+    assert got["gen_layer_visits"] == o.gen_layer_visits and got["refill_layer_visits"] == o.refill_layer_visits
+    print(f"{name} literal={literal}: worst {p.worst:.2e}, tokens checked {p.token_checks}, skipped {p.token_skips}")
+
+
+def test_exdy_switching_n_early_at_cycle_boundaries():
+    """n_early may change whenever no token awaits refill (after a full step), not in between."""
+    sh = di.ModelShape(6, 64, 4, 2, 64, 96, 61, dtype="fp32")
+    blob = di.make_weight_blob(sh, seed=12, std=0.05, gain_sigma=0.2)
+    prompts = di.make_prompts(sh.vocab, 1, 6, seed=2)
+    toks = forced_string(sh.vocab, 1, prompts, 40)
+    p = Pair(sh, blob, 64)
+    p.prefill(prompts)
+    for n_early in (2, 0, 3, 1):
+        s = p.eng.state()
+        assert s["n_tok"] == s["n_front"]
+        p.eng.set_n_early(n_early)
+        p.n_early = n_early
+        for _ in range(3):                       # two late steps, then the full step that refills them
+            p.step_forced(3, 2, toks)
+    assert p.worst < TOL_F32, p.worst
+    p.step_forced(3, 2, toks)                    # a late step: its token now awaits refill
+    with pytest.raises(pkg.DmtdError):
+        p.eng.set_n_early(0)
+    with pytest.raises(pkg.DmtdError):
+        p.eng.decode_cycle(3, 6)                 # n_early + n_late > n_layers
 
 
 def test_changing_tau_and_whole_cycle_calls():
