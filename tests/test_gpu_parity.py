@@ -67,6 +67,11 @@ SHAPES = {
     "tau6": (di.ModelShape(3, 64, 4, 2, 64, 96, 50, dtype="fp32"), 2, 5, 20, 6, 1),
     "bf16_small": (di.ModelShape(4, 256, 8, 2, 128, 512, 1000, dtype="bf16"), 2, 300, 12, 3, 2),
     "bf16_hd64": (di.ModelShape(3, 128, 4, 2, 64, 256, 515, dtype="bf16"), 1, 270, 9, 2, 1),
+    # many rows through the tiled projection kernel (36 rows in full steps, 18 in late steps and in the LM head), with tile
+    # counts that leave waves and blocks partly empty (12, 20, 40 tiles) and a vocabulary that is no multiple of 16
+    "bf16_batch18_ragged_tiles": (di.ModelShape(3, 192, 6, 2, 64, 320, 515, dtype="bf16"), 18, 20, 7, 2, 1),
+    # 80 rows: two passes of the tiled kernel (64 + 16)
+    "bf16_batch20_two_passes": (di.ModelShape(2, 128, 4, 2, 64, 256, 203, dtype="bf16"), 20, 18, 9, 4, 1),
 }
 
 
