@@ -34,7 +34,30 @@ constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per s
 constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
 constexpr int kGemmRows = 64;        // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
-constexpr int kMfmaPFGateUp = 8;     // the same for gate/up: with the two activation planes 10 steps no longer fit 128 registers (two blocks per CU)
+// Waves that split K for one matrix (NW) and k-steps a wave keeps in flight as a rolling window (PF), per projection;
+// NW = 0: the one-round rule of launch_mfma with kMfmaPF.  Defaults from sweeps at 4B shapes on MI355X (us per launch,
+// 3 rows, against the one-round rule): gate/up 20.0 (20.5), down 12.7 (14.3), O 8.2 (8.4), LM head 111.7 (136.7);
+// rolling windows did not help the QKV projection.  The macros exist so a sweep can override them at build time.
+#ifndef DMTD_GU_NW
+#define DMTD_GU_NW 4
+#define DMTD_GU_PF 4
+#endif
+#ifndef DMTD_DN_NW
+#define DMTD_DN_NW 16
+#define DMTD_DN_PF 5
+#endif
+#ifndef DMTD_O_NW
+#define DMTD_O_NW 16
+#define DMTD_O_PF 4
+#endif
+#ifndef DMTD_LM_NW
+#define DMTD_LM_NW 5
+#define DMTD_LM_PF 4
+#endif
+#ifndef DMTD_Q_NW
+#define DMTD_Q_NW 0
+#define DMTD_Q_PF 5
+#endif
 constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter runs put 8 waves on a tile (measured 8.3 us instead of 9.3 us at 4B shapes)
 
 thread_local std::string g_create_error;
@@ -256,18 +279,20 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
 // nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4, 5}) that lets a wave
 // hold its k-range in one round of PF k-steps, else the largest with several rounds.
 // More than 16 rows go through the LDS-tiled kernel, 64 per pass (each pass streams the matrix once).
-template <int EPI, bool NORM, int PF = kMfmaPF>
+template <int EPI, bool NORM, int PF = kMfmaPF, int ROLL_NW = 0>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
   constexpr int MATS = EPI == EPI_SWIGLU ? 2 : 1;
   const int nw_max = EPI == EPI_SWIGLU ? 5 : 8;
   int nw = 2;
   while (nw < nw_max && (KS + nw - 1) / nw > PF) nw = (EPI == EPI_SWIGLU && nw == 4) ? 5 : nw * 2;
+  // ROLL_NW: a fixed number of waves per matrix, each keeping a rolling window of PF k-steps in flight
+  if (ROLL_NW > 0) nw = ROLL_NW;
   const dim3 grid((a.N + 15) / 16);
   // The one-tile-per-block kernel keeps all rows (both planes) in LDS: comfortably (two blocks per CU) in general,
   // up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway.  Rows that do not
   // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to 64 rows.
-  const size_t lds_rows = (size_t)2 * (rows < kMfmaRows ? rows : kMfmaRows) * a.K * 2;
+  const size_t lds_rows = (size_t)(rows < kMfmaRows ? rows : kMfmaRows) * ((size_t)4 * a.K + (NORM ? (size_t)a.n_parts * 4 : 0));
   const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
   if (!fits) {
     const int n_tiles = (a.N + 15) / 16;
@@ -319,10 +344,10 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
     if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
     if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
     if (a.amax) g.amax = a.amax + m0;
-    const size_t lds = (size_t)2 * g.M * a.K * 2;      // the rows, both planes
+    const size_t lds = (size_t)2 * g.M * a.K * 2 + (NORM ? (size_t)g.M * a.n_parts * 4 : 0);   // the rows, both planes; partial sums of squares
 #define DMTD_LAUNCH_MFMA(NWT_)                                                                                            \
     do {                                                                                                                  \
-      auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_>;                                                            \
+      auto kern = gemv_mfma_kernel<EPI, NORM, PF, NWT_, (ROLL_NW > 0)>;                                             \
       static bool big_lds = false;                                                                                        \
       if (lds > 48 * 1024 && !big_lds) {                                                                                  \
         hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024);   \
@@ -331,7 +356,8 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       }                                                                                                                   \
       hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g);                                                 \
     } while (0)
-    if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
+    if constexpr (ROLL_NW > 0) DMTD_LAUNCH_MFMA(ROLL_NW * MATS);
+    else if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);
     else if (nw == 4) DMTD_LAUNCH_MFMA(4 * MATS);
     else if (nw == 5) {
       if constexpr (EPI == EPI_SWIGLU) DMTD_LAUNCH_MFMA(10);
@@ -341,6 +367,27 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
 #undef DMTD_LAUNCH_MFMA
   }
   return hipGetLastError();
+}
+
+hipError_t launch_lmhead(dmtd_ctx* c, MfmaArgs a, int rows) {
+  if constexpr (DMTD_LM_NW > 0) return launch_mfma<EPI_LOGITS, true, DMTD_LM_PF, DMTD_LM_NW>(c, a, rows);
+  else return launch_mfma<EPI_LOGITS, true>(c, a, rows);
+}
+hipError_t launch_qkv(dmtd_ctx* c, MfmaArgs a, int rows) {
+  if constexpr (DMTD_Q_NW > 0) return launch_mfma<EPI_STORE, true, DMTD_Q_PF, DMTD_Q_NW>(c, a, rows);
+  else return launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows);
+}
+hipError_t launch_down(dmtd_ctx* c, MfmaArgs a, int rows) {
+  if constexpr (DMTD_DN_NW > 0) return launch_mfma<EPI_RESID, false, DMTD_DN_PF, DMTD_DN_NW>(c, a, rows);
+  else return launch_mfma<EPI_RESID, false>(c, a, rows);
+}
+hipError_t launch_oproj(dmtd_ctx* c, MfmaArgs a, int rows) {
+  if constexpr (DMTD_O_NW > 0) return launch_mfma<EPI_RESID, false, DMTD_O_PF, DMTD_O_NW>(c, a, rows);
+  else return launch_mfma<EPI_RESID, false>(c, a, rows);
+}
+hipError_t launch_gateup(dmtd_ctx* c, MfmaArgs a, int rows) {
+  if constexpr (DMTD_GU_NW > 0) return launch_mfma<EPI_SWIGLU, true, DMTD_GU_PF, DMTD_GU_NW>(c, a, rows);
+  else return launch_mfma<EPI_SWIGLU, true>(c, a, rows);
 }
 
 // ------------------------------------------------------------------------- attention
@@ -500,25 +547,25 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
     // a2: RMSNorm + fused QKV projection
     a.W = s.qkv; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
-    if ((e = launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows)) != hipSuccess) return e;
+    if ((e = launch_qkv(c, a, rows)) != hipSuccess) return e;
     // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge (output packed for the O projection)
     if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, ab_lo, sel, offset, r)) != hipSuccess) return e;
     // a5: O projection + residual; emits the MLP norm's input
     a = MfmaArgs{};
     a.W = s.o; a.xb = ab; a.xb_lo = ab_lo; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
     a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
-    if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+    if ((e = launch_oproj(c, a, rows)) != hipSuccess) return e;
     R.n_parts = tiles_d;
     // a6: RMSNorm + gate/up + SwiGLU
     a = MfmaArgs{};
     a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts;
     a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.yb = ub; a.yb_lo = ub_lo; a.ldyb = ff;
-    if ((e = launch_mfma<EPI_SWIGLU, true>(c, a, rows)) != hipSuccess) return e;
+    if ((e = launch_gateup(c, a, rows)) != hipSuccess) return e;
     // a7: down projection + residual; emits the next layer's (or the final) norm input
     a = MfmaArgs{};
     a.W = s.down; a.xb = ub; a.xb_lo = ub_lo; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
     a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp; a.ssp_ld = c->ssp_ld;
-    if ((e = launch_mfma<EPI_RESID, false>(c, a, rows)) != hipSuccess) return e;
+    if ((e = launch_down(c, a, rows)) != hipSuccess) return e;
     R.n_parts = tiles_d;
     return hipSuccess;
   }
@@ -556,7 +603,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
     a.W = c->lm_head_sw; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
     a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
     a.amax = amax; a.amax_ld = cf.max_batch;
-    e = launch_mfma<EPI_LOGITS, true>(c, a, n_rows);
+    e = launch_lmhead(c, a, n_rows);
   } else {
     GemvArgs a{};
     a.eps = cf.rms_eps;
@@ -775,19 +822,19 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     switch (kind) {
       case DMTD_K_QKV:
         a.W = s.qkv; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = 1; a.y = qkv; a.ldy = nqkv;
-        return launch_mfma<EPI_STORE, true, kMfmaPFQkv>(c, a, rows);
+        return launch_qkv(c, a, rows);
       case DMTD_K_OPROJ:
         a.W = s.o; a.xb = ab; a.xb_lo = ab_lo; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
         a.g_next = (const bf16_t*)w.mlp_norm; a.ssp_next = R.ssp;
-        return launch_mfma<EPI_RESID, false>(c, a, rows);
+        return launch_oproj(c, a, rows);
       case DMTD_K_GATEUP:
         a.W = s.gate; a.W2 = s.up; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = ff; a.K = d; a.ssp = R.ssp; a.n_parts = (d + 15) / 16;
         a.yb = ub; a.yb_lo = ub_lo; a.ldyb = ff;
-        return launch_mfma<EPI_SWIGLU, true>(c, a, rows);
+        return launch_gateup(c, a, rows);
       default:
         a.W = s.down; a.xb = ub; a.xb_lo = ub_lo; a.ldxb = ff; a.N = d; a.K = ff; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
         a.g_next = (const bf16_t*)norm_gain_for_layer(c, l + 1); a.ssp_next = R.ssp;
-        return launch_mfma<EPI_RESID, false>(c, a, rows);
+        return launch_down(c, a, rows);
     }
   }
   float* attn = (float*)(c->ws + c->o.attn);

@@ -89,19 +89,19 @@ struct MfmaArgs {
 };
 
 // The block first copies the M packed activation rows (both planes) into LDS (dynamic shared
-// memory, 2 * M * K * 2 bytes) and the waves take their B operands from there; the host sends rows
+// memory, 2 * M * K * 2 bytes, plus M * n_parts * 4 for the partial sums of squares if NORM) and the
+// waves take their B operands from there; the host sends rows
 // that do not fit there to the LDS-tiled kernel (gemm_mfma.hpp).
-template <int EPI, bool NORM, int PF, int NWT>   // NWT: waves per block (all matrices)
+template <int EPI, bool NORM, int PF, int NWT, bool ROLL = false>   // NWT: waves per block (all matrices)
 __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   extern __shared__ float4 dyn_smem[];
-  bf16_t* xs = (bf16_t*)dyn_smem;                        // [2 planes][M][K]
+  bf16_t* xs = (bf16_t*)dyn_smem;                        // [2 planes][M][K], then (NORM) M * n_parts floats
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int nw = NWT / MATS;                         // waves that split K for one matrix
   static_assert(nw >= 1 && nw <= MFMA_MAX_WAVES, "waves per tile");
   __shared__ float red[MATS][nw][16][17];               // [matrix][wave][column][row], padded
   __shared__ float ss_s[16][17];
-  constexpr int SS_ITEMS = 16 * 256;                    // partial sums staged in LDS (hidden sizes up to 4096)
-  __shared__ float ss_items[NORM ? SS_ITEMS : 1];
+  float* ss_items = (float*)(xs + (size_t)2 * a.M * a.K);   // NORM: the producer's partial sums [n_parts][M], behind the rows
   __shared__ float rs_s[16];
   __shared__ unsigned long long key_s[16];
   const int tid = threadIdx.x, lane = tid & 63, wall = tid >> 6;
@@ -116,13 +116,13 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   const bool colact = r < M;
   const int ldxs = K;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = acc;
-  constexpr bool TWO_ACC = EPI == EPI_RESID;      // where registers allow (one block per CU)
+  constexpr bool TWO_ACC = EPI == EPI_RESID && !ROLL;      // where registers allow (one block per CU)
 
   // small loads first (they return first): the B rows for LDS and the partial sums of squares
   constexpr int NT = 64 * NWT;
   // registers for the early activation loads: residual projections run one block per CU (few, wide tiles) and can
   // afford to cover long rows; the others stay within 128 registers (two 8-wave blocks per CU)
-  constexpr int NBST = EPI == EPI_RESID ? 16 : 3;
+  constexpr int NBST = EPI == EPI_RESID ? (ROLL ? 8 : 16) : 3;
   u32x4 bst[NBST];
   // the rows follow each other in memory (ldxb == K); LDS holds them the same way, the low
   // plane behind the high one, so a 16-byte chunk's source and destination are linear in its index
@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   if (NORM) {
     // the producer's partial sums of squares, M * n_parts floats, fetched by all threads while the weights fly
     const int n_items = M * a.n_parts;
-    for (int i = tid; i < n_items && i < SS_ITEMS; i += NT) ss_items[i] = a.ssp[(size_t)(i / M) * a.ssp_ld + (i % M)];
+    for (int i = tid; i < n_items; i += NT) ss_items[i] = a.ssp[(size_t)(i / M) * a.ssp_ld + (i % M)];
   }
 #pragma unroll
   for (int j = 0; j < NBST; ++j) {
@@ -176,8 +176,36 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   __syncthreads();
 
   for (int base = s0; base < s1; base += PF) {           // one round unless the wave's k-range exceeds PF steps
-    if (base != s0) load_a(base);
-    if (TWO_ACC) {
+    if (!ROLL && base != s0) load_a(base);
+    if (ROLL) {
+      // rolling window: a k-step's weights are used for both planes at once and its registers are refilled
+      // at once with the step PF ahead, so the wave keeps PF k-steps in flight through its whole k-range
+      const bf16_t* xrow = xs + (size_t)(colact ? r : 0) * ldxs + kg * 8;
+      const bf16_t* xrow_lo = xrow + (size_t)M * ldxs;
+#pragma unroll
+      for (int i = 0; i < PF; ++i) {
+        const int s = base + i;
+        u32x4 b0 = {0, 0, 0, 0}, b1 = b0, c0 = b0, c1 = b0;
+        if (s < s1 && colact) {
+          c0 = *(const u32x4*)(xrow_lo + (size_t)s * 64);
+          c1 = *(const u32x4*)(xrow_lo + (size_t)s * 64 + 32);
+          b0 = *(const u32x4*)(xrow + (size_t)s * 64);
+          b1 = *(const u32x4*)(xrow + (size_t)s * 64 + 32);
+        }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, c0), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, c1), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
+        const int sn = s + PF;
+        if (sn < s1) {
+          A[i][0] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)sn * 1024));
+          A[i][1] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)sn * 1024 + 512));
+        } else {
+          A[i][0] = u32x4{0, 0, 0, 0}; A[i][1] = A[i][0];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else if (TWO_ACC) {
       // registers to spare: both planes of a k-step together, each into its own accumulator, so the
       // matrix-core work keeps pace with the arriving weights
       const bf16_t* xrow = xs + (size_t)(colact ? r : 0) * ldxs + kg * 8;
@@ -230,10 +258,7 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
       const int c = t >> 4, j = t & 15;
       float s = 0.f;
       if (c < M) {
-        for (int p = j; p < a.n_parts; p += 16) {
-          const int i = p * M + c;
-          s += i < SS_ITEMS ? ss_items[i] : a.ssp[(size_t)p * a.ssp_ld + c];
-        }
+        for (int p = j; p < a.n_parts; p += 16) s += ss_items[p * M + c];
       }
       ss_s[c][j] = s;
     }
