@@ -247,6 +247,30 @@ def masked_forward(tokens, mask, n_late: int, w: dict, cfg: OracleConfig, n_earl
     return lm_logits(h, w, cfg)
 
 
+def training_mask(n: int, tau: int) -> np.ndarray:
+    """Eq. 3: position ``i`` is a full position (m_i = 1) exactly when ``i mod tau == 0``."""
+    return np.arange(n) % tau == 0
+
+
+def next_token_nll(logits: np.ndarray, tokens) -> np.ndarray:
+    """Summands of Eq. 6: ``nll[i] = CrossEntropy(z_i, x_{i+1}) = log(sum_v exp z_i[v]) - z_i[x_{i+1}]``
+    for every position ``i`` that has a successor in ``tokens`` (``len(tokens) - 1`` values)."""
+    z = np.asarray(logits)
+    t = np.asarray(tokens)
+    n = len(t) - 1
+    out = np.empty(n, dtype=z.dtype)
+    for i in range(n):
+        row = z[i]
+        top = row.max()
+        out[i] = top + np.log(np.exp(row - top).sum()) - row[t[i + 1]]
+    return out
+
+
+def next_token_loss(logits: np.ndarray, tokens) -> float:
+    """Eq. 6: the mean of the cross entropies of ``z_i`` against ``x_{i+1}`` over the positions that have a successor."""
+    return float(next_token_nll(logits, tokens).mean())
+
+
 def vanilla_forward(tokens, w: dict, cfg: OracleConfig) -> np.ndarray:
     """Ordinary causal forward over the whole sequence (every position full)."""
     cfg0 = dataclasses.replace(cfg, full_pos_add_embed=False)

@@ -312,6 +312,55 @@ def test_training_mask_of_eq3_is_the_inference_mask_for_aligned_prompts():
     assert O.inference_mask(10, 1, 3).astype(int).tolist() == [1, 0, 0, 1, 0, 0, 1, 0, 0, 1]  # the pattern Eq. 3's text prints
 
 
+def test_training_mask_is_eq3_and_prints_the_papers_pattern():
+    """Sec. 2.1 prints the tau = 3 pattern [1,0,0,1,0,0,1,0,0,...] for Eq. 3."""
+    assert O.training_mask(9, 3).astype(int).tolist() == [1, 0, 0, 1, 0, 0, 1, 0, 0]
+    assert O.training_mask(5, 1).all()
+    assert O.training_mask(6, 4).astype(int).tolist() == [1, 0, 0, 0, 1, 0]
+
+
+def test_next_token_loss_of_eq6():
+    """Eq. 6 against the library cross entropy, closed forms, and planted mistakes (unshifted or wrongly signed)."""
+    rng = np.random.default_rng(5)
+    n, V = 12, 37
+    z = rng.normal(size=(n, V)) * 3.0
+    toks = rng.integers(0, V, size=n)
+    nll = O.next_token_nll(z, toks)
+    assert nll.shape == (n - 1,)
+    lib = torch.nn.functional.cross_entropy(torch.from_numpy(z[:-1]), torch.from_numpy(toks[1:].astype(np.int64)), reduction="none").numpy()
+    assert np.abs(nll - lib).max() < 1e-12
+    assert abs(O.next_token_loss(z, toks) - lib.mean()) < 1e-12
+    # closed forms: equal logits give log V whatever the target; a shift of a row changes nothing;
+    # a dominant target logit gives a loss near zero, a dominant wrong logit gives the gap
+    assert np.abs(O.next_token_nll(np.zeros((4, V)), [0, 5, 9, 36]) - math.log(V)).max() < 1e-14
+    assert np.abs(O.next_token_nll(z + 100.0 * rng.normal(size=(n, 1)), toks) - nll).max() < 1e-9
+    big = np.zeros((2, V)); big[0, 7] = 50.0
+    assert O.next_token_nll(big, [3, 7])[0] < 1e-15 + (V - 1) * math.exp(-50.0) * 1.0001
+    assert abs(O.next_token_nll(big, [3, 8])[0] - 50.0) < 1e-12
+    # the values survive large magnitudes (max subtraction)
+    assert np.isfinite(O.next_token_nll(z * 1e3, toks)).all()
+    # planted mistakes are visible to the library pin: target x_i instead of x_{i+1}; wrong sign
+    unshifted = np.array([-np.log(np.exp(z[i] - z[i].max()).sum()) - z[i].max() + z[i][toks[i]] for i in range(n - 1)]) * -1.0
+    assert np.abs(unshifted - lib).max() > 0.1
+    assert np.abs(-nll - lib).max() > 0.1
+
+
+def test_masked_forward_loss_uses_the_masked_logits():
+    """Eq. 6 on the logits of Eqs. 1-5: with tau = 1 (every position full) it is the ordinary next-token loss of the
+    Hugging Face model's logits; with tau > 1 it differs (in-cycle positions never saw the front layers)."""
+    _, cfg, w = make()
+    toks = di.make_prompts(TINY.vocab, 1, 24, seed=11)[0]
+    z1 = O.masked_forward(toks, O.training_mask(len(toks), 1), 2, w, cfg)
+    van = O.vanilla_forward(toks, w, cfg)
+    assert np.abs(z1 - van).max() < 1e-11
+    m = hf_model(TINY, w)
+    with torch.no_grad():
+        out = m(torch.from_numpy(toks.astype(np.int64))[None], labels=torch.from_numpy(toks.astype(np.int64))[None])
+    assert abs(O.next_token_loss(z1, toks) - float(out.loss)) < 2e-6   # the library computes its loss in float32
+    z3 = O.masked_forward(toks, O.training_mask(len(toks), 3), 2, w, cfg)
+    assert abs(O.next_token_loss(z3, toks) - O.next_token_loss(z1, toks)) > 1e-3
+
+
 def test_fig3_schedule():
     want = []
     for line in open(os.path.join(GOLDEN, "fig3_schedule.txt")):
