@@ -161,6 +161,23 @@ int dmtd_time_kernel(dmtd_ctx* ctx, int32_t kind, int32_t rows, int32_t reps, fl
  * Errors: DMTD_EINVAL (n_early outside [0, n_layers - 1]), DMTD_ESTATE. */
 int dmtd_set_n_early(dmtd_ctx* ctx, int32_t n_early);
 
+/* Whole-sequence masked forward (Sec. 2.1, Eqs. 1-5) and next-token loss (Eq. 6): the form the method is trained in, and
+ * a teacher-forced scorer.  Every position of every sequence passes the encoding and thinking layers (the first
+ * n_layers - n_late layers); the decoding layers read, at position i, the thinking output where mask[i] != 0 (a full
+ * position) and the raw token embedding elsewhere (Eq. 4; with n_early > 0 the encoding layers' output; with
+ * full_pos_add_embed the literal sum); the LM head (Eq. 5) follows at every position.  With
+ * mask[i] = (i mod tau == 0) this is Eq. 3; with the mask cycle decoding realises (all prompt positions, then every
+ * tau-th) the logits equal those of dmtd_prefill + teacher-forced dmtd_decode_cycle at the same positions.
+ * tokens: HOST int32 [batch, n] row-major.  mask: HOST uint8 [n], shared by the sequences.
+ * nll: HOST float32 [batch, n] or NULL: nll[b, i] = CrossEntropy(z_i, tokens[b, i+1]) for i < n-1, 0 for i = n-1.
+ * best: HOST int32 [batch, n] or NULL: argmax of z_i (lowest index among equal maxima).
+ * logits: HOST float32 [batch, n, vocab] or NULL (logits_elems >= batch*n*vocab): every position's logits.
+ * loss: HOST float32 [batch] or NULL: Eq. 6, the mean of nll[b, 0..n-2].
+ * Needs an empty context (fresh or reset) and n <= max_seq_len; uses the KV caches as scratch and leaves the context empty.
+ * Errors: DMTD_EINVAL, DMTD_ESTATE (context holds a sequence; dry run), DMTD_ECAPACITY, DMTD_EHIP. */
+int dmtd_masked_forward(dmtd_ctx* ctx, const int32_t* tokens, int32_t batch, int32_t n, const uint8_t* mask, int32_t n_late,
+                        float* nll, int32_t* best, float* logits, size_t logits_elems, float* loss);
+
 /* Back to the state right after dmtd_create (caches are treated as empty). */
 int dmtd_reset(dmtd_ctx* ctx);
 

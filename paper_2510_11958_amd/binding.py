@@ -69,6 +69,9 @@ def load_library():
     lib.dmtd_time_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
     lib.dmtd_set_n_early.restype = C.c_int
     lib.dmtd_set_n_early.argtypes = [C.c_void_p, C.c_int32]
+    lib.dmtd_masked_forward.restype = C.c_int
+    lib.dmtd_masked_forward.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, C.c_int32, P(C.c_uint8), C.c_int32, P(C.c_float),
+                                        P(C.c_int32), P(C.c_float), C.c_size_t, P(C.c_float)]
     lib.dmtd_reset.restype = C.c_int
     lib.dmtd_reset.argtypes = [C.c_void_p]
     lib.dmtd_destroy.restype = None
@@ -221,6 +224,27 @@ class Engine:
     def set_n_early(self, n_early: int):
         """ExDy variant: in-cycle tokens also pass the first ``n_early`` layers (0 = plain method)."""
         self._check(self.lib.dmtd_set_n_early(self._h, int(n_early)))
+
+    def masked_forward(self, tokens, mask, n_late: int, want_logits: bool = False) -> dict:
+        """Whole-sequence masked forward (Eqs. 1-5) with the Eq. 6 loss; returns ``nll`` [batch, n], ``best`` [batch, n],
+        ``loss`` [batch] and, if asked for, ``logits`` [batch, n, vocab]."""
+        t = np.ascontiguousarray(np.atleast_2d(np.asarray(tokens)), dtype=np.int32)
+        m = np.ascontiguousarray(np.asarray(mask), dtype=np.uint8)
+        B, n = t.shape
+        if m.shape != (n,):
+            raise ValueError("mask must have one entry per position")
+        nll = np.empty((B, n), np.float32)
+        best = np.empty((B, n), np.int32)
+        loss = np.empty(B, np.float32)
+        logits = np.empty((B, n, self.cfg.vocab), np.float32) if want_logits else None
+        fp = C.POINTER(C.c_float)
+        self._check(self.lib.dmtd_masked_forward(
+            self._h, _i32p(t), B, n, m.ctypes.data_as(C.POINTER(C.c_uint8)), n_late, nll.ctypes.data_as(fp), _i32p(best),
+            logits.ctypes.data_as(fp) if want_logits else None, logits.size if want_logits else 0, loss.ctypes.data_as(fp)))
+        out = {"nll": nll, "best": best, "loss": loss}
+        if want_logits:
+            out["logits"] = logits
+        return out
 
     def reset(self):
         self._check(self.lib.dmtd_reset(self._h))

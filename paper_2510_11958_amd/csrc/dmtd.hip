@@ -76,6 +76,7 @@ struct Ws {   // device workspace carve-up (byte offsets)
   size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
   size_t gemm_part;                            // K-split partial sums of the tiled kernel
   size_t pend_enc, enc_tmp;                    // ExDy: stored encoding outputs of pending tokens; of a prefill chunk
+  size_t mask, logits_rows, amax_rows, nll, best, loss;   // whole-sequence masked forward: mask, a chunk's logits and keys, per-position results
   size_t total;
 };
 
@@ -179,6 +180,12 @@ Ws layout(const dmtd_config& c) {
   w.pend_enc = take(B * kMaxTau * d * 4);
   w.enc_tmp = take(rows * d * 4);
   w.rope_tab = take(S * (hd / 2) * 8);                 // (cos, sin) per position and frequency
+  w.mask = take(S * 4);
+  w.logits_rows = take(rows * (size_t)c.vocab * 4);
+  w.amax_rows = take((size_t)AMAX_CELLS * rows * 8);
+  w.nll = take(B * S * 4);
+  w.best = take(B * S * 4);
+  w.loss = take(B * 4);
   if (c.dtype == DMTD_DTYPE_BF16) {
     const size_t parts = (d + 15) / 16;
     w.xb = take(rows * d * 2 * 2);                     // high and low planes
@@ -593,25 +600,29 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   return gemv_rows<float, EPI_RESID, false>(c, a, rows);
 }
 
+// a9, first part: final RMSNorm + LM head (Eq. 5) of n_rows rows into logits [n_rows, vocab], selection keys into amax
+hipError_t head_logits(dmtd_ctx* c, const Rows& R, int n_rows, float* logits, unsigned long long* amax, int amax_ld) {
+  const dmtd_config& cf = c->cfg;
+  if (c->packed) {
+    MfmaArgs a{};
+    a.W = c->lm_head_sw; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
+    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.y = logits; a.ldy = cf.vocab;
+    a.amax = amax; a.amax_ld = amax_ld;
+    return launch_lmhead(c, a, n_rows);
+  }
+  GemvArgs a{};
+  a.eps = cf.rms_eps;
+  a.W = c->lm_head; a.gain = c->final_norm; a.x = R.h; a.ldx = cf.hidden;
+  a.y = logits; a.ldy = cf.vocab; a.N = cf.vocab; a.K = cf.hidden;
+  a.amax = amax;
+  return gemv_rows<float, EPI_LOGITS, true>(c, a, n_rows);
+}
+
 // a9: final RMSNorm + LM head + greedy selection for one row per sequence; then the step's bookkeeping
 hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int n_rows) {
   const dmtd_config& cf = c->cfg;
   unsigned long long* amax = (unsigned long long*)(c->ws + c->o.amax);
-  hipError_t e;
-  if (c->packed) {
-    MfmaArgs a{};
-    a.W = c->lm_head_sw; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = cf.hidden; a.N = cf.vocab; a.K = cf.hidden; a.ssp = R.ssp; a.n_parts = R.n_parts;
-    a.ssp_ld = c->ssp_ld; a.eps = cf.rms_eps; a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab;
-    a.amax = amax; a.amax_ld = cf.max_batch;
-    e = launch_lmhead(c, a, n_rows);
-  } else {
-    GemvArgs a{};
-    a.eps = cf.rms_eps;
-    a.W = c->lm_head; a.gain = c->final_norm; a.x = R.h; a.ldx = cf.hidden;
-    a.y = (float*)(c->ws + c->o.logits); a.ldy = cf.vocab; a.N = cf.vocab; a.K = cf.hidden;
-    a.amax = amax;
-    e = gemv_rows<float, EPI_LOGITS, true>(c, a, n_rows);
-  }
+  hipError_t e = head_logits(c, R, n_rows, (float*)(c->ws + c->o.logits), amax, cf.max_batch);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(n_rows >= 16 ? 1024 : 64 * n_rows), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
                      dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens);
@@ -786,6 +797,44 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
   }
   if ((e = take_last_rows(c, front, late, r_last, 0, POS_EXPLICIT, p_last, cf.n_layers)) != hipSuccess) return e;
   return run_head(c, late, 1, 1, c->batch);   // state goes from P-1 to n_tok = n_front = P
+}
+
+// One chunk of the whole-sequence masked forward (Sec. 2.1, Eqs. 1-5): positions p0 .. p0+r-1 of every sequence pass the
+// encoding and thinking layers, Eq. 4 picks each position's input to the decoding layers by its mask bit, the
+// decoding layers and the LM head follow for every row, and a row kernel takes the Eq. 6 summands and the argmax.
+// Earlier chunks are seen through the KV caches, exactly as later decode steps would see them.
+hipError_t enqueue_masked_chunk(dmtd_ctx* c, int p0, int r, int n, int n_late) {
+  const dmtd_config& cf = c->cfg;
+  const int F = cf.n_layers - n_late, E = c->sched.n_early, rows = c->batch * r;
+  Rows R = front_rows(c);
+  float* enc = (float*)(c->ws + c->o.enc_tmp);
+  hipError_t e;
+  choose_attention(c, p0 + r);
+  if ((e = embed_rows(c, R, POS_EXPLICIT, p0, r, 0)) != hipSuccess) return e;
+  for (int l = 0; l <= F; ++l) {
+    if (E > 0 && l == E &&
+        (e = hipMemcpyAsync(enc, R.h, (size_t)rows * cf.hidden * 4, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess) return e;
+    if (l < F && (e = run_layer(c, l, R, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
+  }
+  const int* mask = (const int*)(c->ws + c->o.mask);
+  if (c->packed) {
+    hipLaunchKernelGGL((mask_combine_kernel<bf16_t, true>), dim3(rows), dim3(256), 0, c->stream, R.h, E > 0 ? (const float*)enc : (const float*)nullptr,
+                       (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, mask, p0, r, cf.hidden, cf.full_pos_add_embed,
+                       (const bf16_t*)norm_gain_for_layer(c, F), R.xb, R.xb_lo, R.ssp);
+    R.n_parts = 1;
+  } else {
+    hipLaunchKernelGGL((mask_combine_kernel<float, false>), dim3(rows), dim3(256), 0, c->stream, R.h, E > 0 ? (const float*)enc : (const float*)nullptr,
+                       (const float*)c->embed, dev_tokens(c), cf.max_seq_len, mask, p0, r, cf.hidden, cf.full_pos_add_embed,
+                       (const bf16_t*)nullptr, (bf16_t*)nullptr, (bf16_t*)nullptr, (float*)nullptr);
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  for (int l = F; l < cf.n_layers; ++l)
+    if ((e = run_layer(c, l, R, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
+  float* logits = (float*)(c->ws + c->o.logits_rows);
+  if ((e = head_logits(c, R, rows, logits, (unsigned long long*)(c->ws + c->o.amax_rows), cf.max_batch * kMaxRows)) != hipSuccess) return e;
+  hipLaunchKernelGGL(nll_rows_kernel, dim3(rows), dim3(1024), 0, c->stream, (const float*)logits, cf.vocab, (const int*)dev_tokens(c), cf.max_seq_len,
+                     p0, r, n, (float*)(c->ws + c->o.nll), (int*)(c->ws + c->o.best));
+  return hipGetLastError();
 }
 
 // One launch of one kernel kind on layer l, for dmtd_time_kernel.  Outputs go to scratch
@@ -1164,6 +1213,64 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
   if (e != hipSuccess) { c->err = std::string("dmtd_time_kernel: ") + hipGetErrorString(e); return DMTD_EHIP; }
   *avg_us = ms * 1000.0f / (float)launches;
   return DMTD_OK;
+}
+
+int dmtd_masked_forward(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t n, const uint8_t* mask, int32_t n_late,
+                        float* nll, int32_t* best, float* logits, size_t logits_elems, float* loss) {
+  if (!c) return DMTD_EINVAL;
+  const dmtd_config& cf = c->cfg;
+  if (!tokens || !mask) { c->err = "null tokens or mask"; return DMTD_EINVAL; }
+  if (batch < 1 || batch > cf.max_batch) { c->err = "batch outside [1, max_batch]"; return DMTD_EINVAL; }
+  if (n < 1) { c->err = "sequence length must be >= 1"; return DMTD_EINVAL; }
+  if (n_late < 1 || n_late > cf.n_layers) { c->err = "n_late must be in [1, n_layers]"; return DMTD_EINVAL; }
+  if (c->sched.n_early + n_late > cf.n_layers) { c->err = "n_early + n_late exceeds the number of layers"; return DMTD_EINVAL; }
+  if (c->sched.n_tok != 0) { c->err = "the masked forward needs an empty context; call dmtd_reset first"; return DMTD_ESTATE; }
+  if (n > cf.max_seq_len) { c->err = "sequence longer than max_seq_len"; return DMTD_ECAPACITY; }
+  if (logits && logits_elems < (size_t)batch * n * cf.vocab) { c->err = "logits buffer too small"; return DMTD_ECAPACITY; }
+  for (size_t i = 0; i < (size_t)batch * n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= cf.vocab) { c->err = "token id outside the vocabulary"; return DMTD_EINVAL; }
+  if (cf.dry_run) { c->err = "no device work in a dry run"; return DMTD_ESTATE; }
+  const int saved_batch = c->batch;
+  c->batch = batch;
+  std::vector<int32_t> m32(n);
+  for (int i = 0; i < n; ++i) m32[i] = mask[i] ? 1 : 0;
+  int rc = DMTD_OK;
+  hipError_t e = hipMemcpy2DAsync(c->ws + c->o.tokens, (size_t)cf.max_seq_len * 4, tokens, (size_t)n * 4, (size_t)n * 4, batch,
+                                  hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(c->ws + c->o.mask, m32.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  for (int p0 = 0; p0 < n && e == hipSuccess; p0 += kPrefillChunk) {
+    const int r = n - p0 < kPrefillChunk ? n - p0 : kPrefillChunk;
+    e = enqueue_masked_chunk(c, p0, r, n, n_late);
+    if (logits && e == hipSuccess) {
+      // the chunk's rows of sequence b follow each other: one copy per sequence, before the next chunk reuses the buffer
+      for (int b = 0; b < batch && e == hipSuccess; ++b)
+        e = hipMemcpyAsync(logits + ((size_t)b * n + p0) * cf.vocab, c->ws + c->o.logits_rows + (size_t)b * r * cf.vocab * 4,
+                           (size_t)r * cf.vocab * 4, hipMemcpyDeviceToHost, c->stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    }
+  }
+  std::vector<float> nll_h((size_t)batch * n), loss_h(batch);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(mean_nll_kernel, dim3(batch), dim3(256), 0, c->stream, (const float*)(c->ws + c->o.nll), cf.max_seq_len, n,
+                       (float*)(c->ws + c->o.loss));
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(loss_h.data(), c->ws + c->o.loss, (size_t)batch * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipMemcpy2DAsync(nll_h.data(), (size_t)n * 4, c->ws + c->o.nll, (size_t)cf.max_seq_len * 4, (size_t)n * 4, batch,
+                                            hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && best) e = hipMemcpy2DAsync(best, (size_t)n * 4, c->ws + c->o.best, (size_t)cf.max_seq_len * 4, (size_t)n * 4, batch,
+                                                    hipMemcpyDeviceToHost, c->stream);
+  // the caches served as scratch: back to the empty state on the device as on the host
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, dev_state(c), 0, 0);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  c->batch = saved_batch;
+  if (e != hipSuccess) { c->err = std::string("dmtd_masked_forward: ") + hipGetErrorString(e); (void)hipStreamSynchronize(c->stream); return DMTD_EHIP; }
+  if (nll) std::memcpy(nll, nll_h.data(), nll_h.size() * 4);
+  if (loss) std::memcpy(loss, loss_h.data(), (size_t)batch * 4);
+  return rc;
 }
 
 int dmtd_set_n_early(dmtd_ctx* c, int32_t n_early) {

@@ -422,4 +422,30 @@ __global__ void __launch_bounds__(256) rows_op_kernel(int mode, float* __restric
   }
 }
 
+// Eq. 4 over the rows of one chunk of a whole-sequence forward (row b*r+i = position p0+i of sequence b), in place
+// on the thinking layers' output h: a full position (mask 1) keeps h_think, any other position takes h_emb, the raw
+// embedding of its token (ExDy variant: enc, the stored output of the encoding layers); under the literal reading
+// the result is h_emb (or h_enc) + mask * h_think.  PACK: also the packed input of the decoding layers' first norm.
+template <typename WT, bool PACK>
+__global__ void __launch_bounds__(256) mask_combine_kernel(float* __restrict__ h, const float* __restrict__ enc, const WT* __restrict__ table,
+                                                           const int* __restrict__ tokens, int s_max, const int* __restrict__ mask,
+                                                           int p0, int r, int d, int literal, const bf16_t* __restrict__ gain,
+                                                           bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp) {
+  const int row = blockIdx.x, b = row / r, pos = p0 + row % r;
+  const bool full = mask[pos] != 0;
+  float* o = h + (size_t)row * d;
+  const float* e = enc ? enc + (size_t)row * d : nullptr;
+  const WT* t = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
+  if (literal || !full) {
+    for (int k = threadIdx.x; k < d; k += blockDim.x) {
+      const float base = e ? e[k] : Elem<WT>::to_f32(t[k]);
+      o[k] = literal ? base + (full ? o[k] : 0.f) : base;
+    }
+  }
+  if (PACK) {
+    __syncthreads();
+    pack_row_for_norm(o, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);
+  }
+}
+
 }  // namespace dmtd

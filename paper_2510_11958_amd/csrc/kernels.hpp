@@ -198,6 +198,68 @@ __global__ void add_embed_rows_kernel(float* __restrict__ h, const WT* __restric
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += Elem<WT>::to_f32(e[k]);
 }
 
+// Summands of the next-token loss (Eq. 6) and the greedy choice for the rows of one chunk of a whole-sequence
+// forward: row b*r+i of the launch is position p0+i of sequence b; its target is the sequence's next token
+// (none for the last position n-1: the summand is stored as 0).  nll = log(sum_v exp(z_v - max)) + max - z_target,
+// sums taken per thread, per wave and over the waves in a fixed order.  One block of 1024 threads per row.
+__global__ void __launch_bounds__(1024) nll_rows_kernel(const float* __restrict__ logits, int V, const int* __restrict__ tokens, int s_max,
+                                                        int p0, int r, int n, float* __restrict__ nll, int* __restrict__ best) {
+  const int row = blockIdx.x, b = row / r, pos = p0 + row % r;
+  const float* z = logits + (size_t)row * V;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ unsigned long long key_w[16];
+  __shared__ float sum_w[16];
+  __shared__ float top_s;
+  unsigned long long key = 0ull;
+  for (int v = tid; v < V; v += 1024) {
+    const unsigned long long k = argmax_key(z[v], v);
+    if (k > key) key = k;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long other = __shfl_xor(key, o, 64);
+    if (other > key) key = other;
+  }
+  if (lane == 0) key_w[wave] = key;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long k = key_w[0];
+    for (int w = 1; w < 16; ++w) if (key_w[w] > k) k = key_w[w];
+    const int idx = argmax_key_index(k);
+    best[(size_t)b * s_max + pos] = idx;
+    top_s = z[idx];
+  }
+  __syncthreads();
+  const float top = top_s;
+  float s = 0.f;
+  for (int v = tid; v < V; v += 1024) s += __expf(z[v] - top);
+  s = wave_sum(s);
+  if (lane == 0) sum_w[wave] = s;
+  __syncthreads();
+  if (tid == 0) {
+    float tot = 0.f;
+    for (int w = 0; w < 16; ++w) tot += sum_w[w];
+    float out = 0.f;
+    if (pos + 1 < n) out = __logf(tot) + top - z[tokens[(size_t)b * s_max + pos + 1]];
+    nll[(size_t)b * s_max + pos] = out;
+  }
+}
+
+// Eq. 6 per sequence: the mean of the summands of the n-1 positions that have a successor (fixed summation order).
+__global__ void __launch_bounds__(256) mean_nll_kernel(const float* __restrict__ nll, int s_max, int n, float* __restrict__ loss) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ float part[256];
+  float s = 0.f;
+  for (int i = tid; i + 1 < n; i += 256) s += nll[(size_t)b * s_max + i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    float tot = 0.f;
+    for (int t = 0; t < 256; ++t) tot += part[t];
+    loss[b] = n > 1 ? tot / (float)(n - 1) : 0.f;
+  }
+}
+
 }  // namespace dmtd
 
 #include "gemv.hpp"

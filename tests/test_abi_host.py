@@ -207,3 +207,27 @@ def test_long_cycles_refill_all_pending_rows():
     e.decode_cycle(12, 1, max_new=1)
     assert e.trace()[-2:] == [(13, "front", list(range(3, 15))), (13, "late", [14])]
     assert e.state()["n_tok"] == e.state()["n_front"] == 15
+
+
+def test_masked_forward_argument_checks_without_a_gpu():
+    """Argument validation of dmtd_masked_forward runs before any device work (dry-run context)."""
+    e = dry(max_seq_len=16, max_batch=2)
+    ok_t, ok_m = np.ones((2, 8), np.int32), np.ones(8, np.uint8)
+    for toks, mask, n_late, code in [
+            (ok_t, ok_m, 0, pkg.DMTD_EINVAL), (ok_t, ok_m, 5, pkg.DMTD_EINVAL),
+            (np.full((2, 8), 50, np.int32), ok_m, 1, pkg.DMTD_EINVAL),
+            (np.ones((3, 8), np.int32), ok_m, 1, pkg.DMTD_EINVAL),
+            (np.ones((1, 17), np.int32), np.ones(17, np.uint8), 1, pkg.DMTD_ECAPACITY),
+            (ok_t, ok_m, 1, pkg.DMTD_ESTATE)]:             # valid arguments: only the dry run itself is refused
+        with pytest.raises(pkg.DmtdError) as err:
+            e.masked_forward(toks, mask, n_late)
+        assert err.value.code == code
+    e.set_n_early(2)
+    with pytest.raises(pkg.DmtdError) as err:
+        e.masked_forward(ok_t, ok_m, 3)                   # n_early + n_late > n_layers
+    assert err.value.code == pkg.DMTD_EINVAL
+    e.set_n_early(0)
+    e.prefill([[1, 2, 3], [4, 5, 6]])
+    with pytest.raises(pkg.DmtdError) as err:
+        e.masked_forward(ok_t, ok_m, 1)
+    assert err.value.code == pkg.DMTD_ESTATE

@@ -181,6 +181,53 @@ def test_exdy_at_4b_shapes(model_4b, n_early, n_late):
     print(f"E{n_early}D{n_late}: worst {worst:.2e}")
 
 
+def test_masked_forward_at_4b_shape(model_4b):
+    """Whole-sequence masked forward (Eqs. 1-5) and the Eq. 6 summands at the 4B shape, E0D8 and tau = 3 (the paper's
+    default allocation): two sequences of 40 positions with Eq. 3's mask, every position's logits, cross entropy and
+    argmax of both sequences against the float32 oracle's one-shot forward."""
+    sh, blob, ocfg, w32, dev = model_4b
+    B, n, tau, n_late = 2, 40, 3, 8
+    toks = di.make_prompts(sh.vocab, B, n, seed=31)
+    mask = O.training_mask(n, tau)
+    eng = pkg.Engine(engine_config(sh, n + 8, B), dev)
+    got = eng.masked_forward(toks, mask, n_late, want_logits=True)
+    worst = 0.0
+    for b in range(B):
+        ref = O.masked_forward(toks[b], mask, n_late, w32, ocfg).astype(np.float64)
+        for i in range(n):
+            worst = max(worst, norm_err(got["logits"][b, i], ref[i]))
+            if top2_margin(ref[i]) > MARGIN:
+                assert int(got["best"][b, i]) == int(np.argmax(ref[i]))
+        bound = 2 * TOL_BF16 * np.abs(ref).max()
+        assert np.abs(got["nll"][b, :n - 1] - O.next_token_nll(ref, toks[b])).max() < bound
+        assert abs(got["loss"][b] - O.next_token_loss(ref, toks[b])) < bound
+    assert worst < TOL_BF16, worst
+    print(f"masked forward at the 4B shape: worst {worst:.2e}")
+
+
+def test_masked_forward_equals_c3_cycle_decoding(model_4b):
+    """C3 at its full prompt length (P = 1024, tau = 3, n_late = 8), on the GPU alone: the one-shot masked forward over
+    1024 + 24 positions with the mask cycle decoding realises against prefill + 24 teacher-forced decode steps (whose
+    first 8 the test above checks against the oracle).  Property at full size; the oracle is not run here."""
+    wl = di.WORKLOADS["C3"]
+    sh, blob, ocfg, w32, dev = model_4b
+    P, n = wl.prompt_len, wl.prompt_len + 24
+    prompts = di.make_prompts(sh.vocab, 1, P, seed=1)
+    toks = np.stack(forced_string(sh.vocab, 1, prompts, n))
+    eng = pkg.Engine(engine_config(sh, n + 8), dev)
+    one = eng.masked_forward(toks, O.inference_mask(n, P, wl.tau), wl.n_late, want_logits=True)
+    first = eng.prefill(toks[:, :P])
+    assert int(first[0]) == int(one["best"][0, P - 1]) or top2_margin(one["logits"][0, P - 1].astype(np.float64)) <= MARGIN
+    worst = norm_err(eng.logits()[0], one["logits"][0, P - 1].astype(np.float64))
+    for pos in range(P, n):
+        eng.decode_cycle(wl.tau, wl.n_late, max_new=1, forced=toks[:, pos:pos + 1])
+        worst = max(worst, norm_err(eng.logits()[0], one["logits"][0, pos].astype(np.float64)))
+    # the two paths carry different row counts through the projections (16-position chunks vs 1 or 3 rows), so
+    # they differ by the bf16 storage noise of the caches, well inside the tolerance against the oracle
+    assert worst < 0.5 * TOL_BF16, worst
+    print(f"C3 one-shot masked forward vs cycle decoding: worst {worst:.2e}")
+
+
 def test_batch_rows_are_independent_and_identical_prompts_agree(model_4b):
     """Property at any size: a sequence's outputs do not depend on its neighbours in the batch."""
     sh, blob, ocfg, w32, dev = model_4b
