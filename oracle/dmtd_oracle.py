@@ -283,6 +283,37 @@ def plt_closed_form(n_layers: int, n_late: int, tau: int, n_early: int = 0) -> f
     return (n_layers + (tau - 1) * (n_early + n_late)) / (tau * n_layers)
 
 
+# ------------------------------------------------------------ token selection by sampling
+
+def sampling_uniforms(seed: int, seq: int, pos: int, vocab: int) -> np.ndarray:
+    """The ``vocab`` uniform deviates of one draw, one per vocabulary entry, from the counter-based generator of
+    the input module: stream ``(seed, seq * 2^32 + pos)``, entry ``v`` from counter ``v``, the top 23 bits of the
+    64-bit value mapped to the midpoints ``(m + 0.5) / 2^23`` of a 23-bit grid (strictly inside (0, 1), and exactly
+    representable in float32, 2 m + 1 < 2^24, so a float32 implementation draws the same numbers)."""
+    import dmtd_inputs
+    raw = dmtd_inputs.raw_u64(seed, (int(seq) << 32) | int(pos), 0, vocab)
+    return ((raw >> np.uint64(41)).astype(np.float64) + 0.5) / float(1 << 23)
+
+
+def sampling_scores(z: np.ndarray, temperature: float, top_k: int, seed: int, seq: int, pos: int) -> np.ndarray:
+    """Scores whose argmax is a draw from ``softmax(z / temperature)`` restricted to the ``top_k`` largest logits
+    (``top_k <= 0``: no restriction; logits equal to the k-th largest all stay in): ``z_v / temperature + g_v``
+    with independent standard Gumbel deviates ``g_v = -log(-log(u_v))`` (the Gumbel-max identity); entries outside
+    the restriction get ``-inf``."""
+    z = np.asarray(z, dtype=np.float64)
+    u = sampling_uniforms(seed, seq, pos, len(z))
+    s = z / float(temperature) - np.log(-np.log(u))
+    if 0 < top_k < len(z):
+        kth = np.sort(z)[len(z) - top_k]
+        s = np.where(z >= kth, s, -np.inf)
+    return s
+
+
+def sample_token(z: np.ndarray, temperature: float, top_k: int, seed: int, seq: int, pos: int) -> int:
+    """One token drawn for the row at position ``pos`` of sequence ``seq`` (lowest index among equal scores)."""
+    return int(np.argmax(sampling_scores(z, temperature, top_k, seed, seq, pos)))
+
+
 # -------------------------------------------------------- incremental cycle machine
 
 class DmtdOracle:
@@ -316,6 +347,7 @@ class DmtdOracle:
         self.n_late_in_use = None
         self.n_early_in_use = 0
         self.pend_enc: list[np.ndarray] = []   # ExDy: encoding outputs of the tokens that await refill
+        self.last_scores = None           # sampling: the scores whose argmax was the last token
 
     # one block over `rows` new positions with the layer's cache
     def _block(self, l: int, X: np.ndarray, positions: np.ndarray) -> np.ndarray:
@@ -327,11 +359,23 @@ class DmtdOracle:
         attn = causal_attention(q, positions, self.K[l][:ctx], self.V[l][:ctx])
         return _finish_block(lw, X, attn, self.cfg)
 
+    def set_sampling(self, temperature: float, top_k: int = 0, seed: int = 0, seq: int = 0):
+        """Select tokens by sampling (``temperature > 0``) instead of greedily (``temperature <= 0``, the default).
+        ``seq`` is the sequence's index in its batch: it enters the random counter, so that sequences draw
+        independently.  The setting survives ``reset``."""
+        self.sampling = (float(temperature), int(top_k), int(seed), int(seq)) if temperature > 0 else None
+
     def _emit(self, h_row: np.ndarray) -> int:
         z = lm_logits(h_row, self.w, self.cfg)
         self.last_logits = z
         self.step_logits.append(z)
-        return int(np.argmax(z))
+        sampling = getattr(self, "sampling", None)
+        if sampling is None:
+            return int(np.argmax(z))
+        t, k, seed, seq = sampling
+        # the row that emits sits at position n_tok - 1 (the callers have already counted it)
+        self.last_scores = sampling_scores(z, t, k, seed, seq, self.n_tok - 1)
+        return int(np.argmax(self.last_scores))
 
     def prefill(self, tokens, n_late: int | None = None, n_early: int = 0) -> int:
         """All prompt tokens through all layers; returns the first generated token.

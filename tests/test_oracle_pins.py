@@ -361,6 +361,94 @@ def test_masked_forward_loss_uses_the_masked_logits():
     assert abs(O.next_token_loss(z3, toks) - O.next_token_loss(z1, toks)) > 1e-3
 
 
+def test_sampling_uniforms_are_the_generators_top_23_bits():
+    u = O.sampling_uniforms(5, 2, 17, 1000)
+    raw = di.raw_u64(5, (2 << 32) | 17, 0, 1000)
+    assert np.array_equal(u * (1 << 23) - 0.5, (raw >> np.uint64(41)).astype(np.float64))
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert np.array_equal(u.astype(np.float32).astype(np.float64), u)          # exactly representable in float32
+    assert not np.array_equal(u, O.sampling_uniforms(5, 2, 18, 1000))           # another position: another draw
+    assert not np.array_equal(u, O.sampling_uniforms(5, 3, 17, 1000))           # another sequence
+    big = O.sampling_uniforms(1, 0, 0, 200000)
+    assert abs(big.mean() - 0.5) < 3e-3 and abs(big.var() - 1.0 / 12.0) < 2e-3
+
+
+def _draw_frequencies(z, temperature, top_k, n, mutate=None):
+    counts = np.zeros(len(z))
+    for pos in range(n):
+        s = O.sampling_scores(z, temperature, top_k, 99, 0, pos)
+        if mutate is not None:
+            s = mutate(z, pos)
+        counts[int(np.argmax(s))] += 1
+    return counts
+
+
+def test_sampling_draws_from_the_tempered_softmax_over_the_top_k():
+    """Frequencies of 40000 draws (one per position counter) against softmax(z / T) over the k largest logits:
+    Pearson's chi-square statistic below the 0.9999 quantile.  Planted mistakes (temperature multiplied instead of
+    divided, restriction to the k smallest, no restriction) exceed it by far."""
+    from scipy import stats
+    z = np.array([2.0, 0.5, 1.5, -1.0, 0.0, 1.0, -2.0, 0.7])
+    n = 40000
+    for T, k in ((1.0, 0), (0.7, 0), (1.6, 5), (0.5, 3)):
+        keep = np.ones(len(z), bool) if k == 0 else z >= np.sort(z)[len(z) - k]
+        p = np.where(keep, np.exp(z / T), 0.0)
+        p /= p.sum()
+        counts = _draw_frequencies(z, T, k, n)
+        assert counts[~keep].sum() == 0
+        chi2 = (((counts - n * p) ** 2)[keep] / (n * p[keep])).sum()
+        assert chi2 < stats.chi2.ppf(0.9999, keep.sum() - 1), (T, k, chi2)
+    T, k = 0.5, 3
+    keep = z >= np.sort(z)[len(z) - k]
+    p = np.where(keep, np.exp(z / T), 0.0)
+    p /= p.sum()
+    limit = stats.chi2.ppf(0.9999, len(z) - 1)
+
+    def chi2_of(counts):
+        exp = np.maximum(n * p, 1e-9)
+        return (((counts - n * p) ** 2) / exp).sum()
+
+    g = lambda pos: -np.log(-np.log(O.sampling_uniforms(99, 0, pos, len(z))))
+    wrong_temperature = _draw_frequencies(z, T, k, n, lambda zz, pos: np.where(keep, zz * T + g(pos), -np.inf))
+    smallest_k = _draw_frequencies(z, T, k, n, lambda zz, pos: np.where(zz <= np.sort(zz)[k - 1], zz / T + g(pos), -np.inf))
+    unrestricted = _draw_frequencies(z, T, k, n, lambda zz, pos: zz / T + g(pos))
+    for wrong in (wrong_temperature, smallest_k, unrestricted):
+        assert chi2_of(wrong) > 10 * limit
+
+
+def test_sampling_special_cases_and_the_cycle_machine():
+    """top_k = 1 and temperature -> 0 are greedy selection; k >= V is no restriction; ties at the k-th logit stay in;
+    the cycle machine draws at the emitting row's position and sequences draw independently."""
+    rng = np.random.default_rng(3)
+    z = rng.normal(size=50) * 2
+    for pos in range(20):
+        assert O.sample_token(z, 1.3, 1, 7, 0, pos) == int(np.argmax(z))
+        assert O.sample_token(z, 1e-4, 0, 7, 0, pos) == int(np.argmax(z))
+        assert O.sample_token(z, 0.9, 50, 7, 0, pos) == O.sample_token(z, 0.9, 0, 7, 0, pos) == O.sample_token(z, 0.9, 80, 7, 0, pos)
+    tied = np.array([1.0, 3.0, 2.0, 2.0, 0.0])
+    assert np.isfinite(O.sampling_scores(tied, 1.0, 2, 0, 0, 0)).tolist() == [False, True, True, True, False]
+    _, cfg, w = make()
+    toks = di.make_prompts(TINY.vocab, 1, 9, seed=4)[0]
+    runs = []
+    for seq in (0, 0, 1):
+        o = O.DmtdOracle(cfg, w, 64)
+        o.set_sampling(1.5, 8, seed=11, seq=seq)
+        out = [o.prefill(toks)]
+        assert out[0] == O.sample_token(o.last_logits, 1.5, 8, 11, seq, len(toks) - 1)
+        for _ in range(5):
+            got = o.decode_cycle(3, 2)
+            assert got[-1] == O.sample_token(o.last_logits, 1.5, 8, 11, seq, o.n_tok - 1)
+            out += got
+        runs.append(out)
+    assert runs[0] == runs[1] and runs[0] != runs[2]
+    greedy = O.DmtdOracle(cfg, w, 64)
+    g_out = [greedy.prefill(toks)] + sum((greedy.decode_cycle(3, 2) for _ in range(5)), [])
+    assert g_out != runs[0]
+    o = O.DmtdOracle(cfg, w, 64)
+    o.set_sampling(0.0)
+    assert [o.prefill(toks)] + sum((o.decode_cycle(3, 2) for _ in range(5)), []) == g_out
+
+
 def test_fig3_schedule():
     want = []
     for line in open(os.path.join(GOLDEN, "fig3_schedule.txt")):
