@@ -161,6 +161,16 @@ int dmtd_time_kernel(dmtd_ctx* ctx, int32_t kind, int32_t rows, int32_t reps, fl
  * Errors: DMTD_EINVAL (n_early outside [0, n_layers - 1]), DMTD_ESTATE. */
 int dmtd_set_n_early(dmtd_ctx* ctx, int32_t n_early);
 
+/* Token selection.  The paper generates without post-verification and names no sampling rule (Sec. 3.2); greedy
+ * selection is the default here.  With temperature > 0 every later prefill and decode step draws its token from
+ * softmax(z / temperature) restricted to the top_k largest logits (top_k = 0: no restriction; logits equal to the
+ * k-th largest all stay in; top_k = 1 or temperature <= 0: greedy).  The draw for the row at position p of sequence
+ * b is argmax_v z_v / temperature - log(-log(u_v)) (Gumbel-max), u_v = (m + 0.5) / 2^23 with m the top 23 bits of a
+ * counter-based SplitMix64 value keyed by (seed, b * 2^32 + p, v): it does not depend on batch order, graph replay
+ * or earlier draws.  dmtd_logits still returns the unperturbed logits; the setting survives dmtd_reset.
+ * Errors: DMTD_EINVAL (temperature not finite, top_k < 0), DMTD_EHIP. */
+int dmtd_set_sampling(dmtd_ctx* ctx, float temperature, int32_t top_k, uint64_t seed);
+
 /* Whole-sequence masked forward (Sec. 2.1, Eqs. 1-5) and next-token loss (Eq. 6): the form the method is trained in, and
  * a teacher-forced scorer.  Every position of every sequence passes the encoding and thinking layers (the first
  * n_layers - n_late layers); the decoding layers read, at position i, the thinking output where mask[i] != 0 (a full

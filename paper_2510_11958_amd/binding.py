@@ -69,6 +69,8 @@ def load_library():
     lib.dmtd_time_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_float)]
     lib.dmtd_set_n_early.restype = C.c_int
     lib.dmtd_set_n_early.argtypes = [C.c_void_p, C.c_int32]
+    lib.dmtd_set_sampling.restype = C.c_int
+    lib.dmtd_set_sampling.argtypes = [C.c_void_p, C.c_float, C.c_int32, C.c_uint64]
     lib.dmtd_masked_forward.restype = C.c_int
     lib.dmtd_masked_forward.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, C.c_int32, P(C.c_uint8), C.c_int32, P(C.c_float),
                                         P(C.c_int32), P(C.c_float), C.c_size_t, P(C.c_float)]
@@ -224,6 +226,10 @@ class Engine:
     def set_n_early(self, n_early: int):
         """ExDy variant: in-cycle tokens also pass the first ``n_early`` layers (0 = plain method)."""
         self._check(self.lib.dmtd_set_n_early(self._h, int(n_early)))
+
+    def set_sampling(self, temperature: float, top_k: int = 0, seed: int = 0):
+        """Draw tokens from the tempered softmax over the top_k logits (temperature <= 0: greedy, the default)."""
+        self._check(self.lib.dmtd_set_sampling(self._h, float(temperature), int(top_k), int(seed)))
 
     def masked_forward(self, tokens, mask, n_late: int, want_logits: bool = False) -> dict:
         """Whole-sequence masked forward (Eqs. 1-5) with the Eq. 6 loss; returns ``nll`` [batch, n], ``best`` [batch, n],

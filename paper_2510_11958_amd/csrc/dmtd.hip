@@ -112,6 +112,7 @@ struct dmtd_ctx {
   std::vector<LayerW> layers;
   std::vector<LayerSw> sw;
   std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
+  bool sampling = false;      // tokens are drawn (dmtd_set_sampling) instead of taken greedily
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
   int att_bucket = 512;       // attention launches: context bucket (multiple of 512) the key ranges are laid out for
 };
@@ -624,6 +625,11 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
   unsigned long long* amax = (unsigned long long*)(c->ws + c->o.amax);
   hipError_t e = head_logits(c, R, n_rows, (float*)(c->ws + c->o.logits), amax, cf.max_batch);
   if (e != hipSuccess) return e;
+  if (c->sampling && write_tokens) {
+    hipLaunchKernelGGL(sample_kernel, dim3(n_rows), dim3(1024), 0, c->stream, (const float*)(c->ws + c->o.logits), cf.vocab,
+                       (const SampleCfg*)(c->ws + c->o.state + 64), (const DevState*)dev_state(c), amax, AMAX_CELLS, cf.max_batch);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(n_rows >= 16 ? 1024 : 64 * n_rows), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
                      dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens);
   return hipGetLastError();
@@ -745,7 +751,7 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
     HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late * 4096 + c->sched.n_early, c->att_bucket * 2 + (c->share_kv ? 1 : 0));
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late * 4096 + c->sched.n_early + (c->sampling ? (1 << 30) : 0), c->att_bucket * 2 + (c->share_kv ? 1 : 0));
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -1271,6 +1277,20 @@ int dmtd_masked_forward(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32
   if (nll) std::memcpy(nll, nll_h.data(), nll_h.size() * 4);
   if (loss) std::memcpy(loss, loss_h.data(), (size_t)batch * 4);
   return rc;
+}
+
+int dmtd_set_sampling(dmtd_ctx* c, float temperature, int32_t top_k, uint64_t seed) {
+  if (!c) return DMTD_EINVAL;
+  if (!(temperature == temperature) || temperature > 1e30f) { c->err = "temperature must be a finite number"; return DMTD_EINVAL; }
+  if (top_k < 0) { c->err = "top_k must be >= 0"; return DMTD_EINVAL; }
+  const bool on = temperature > 0.f && top_k != 1;      // top_k = 1 is the greedy choice whatever the temperature
+  if (on && !c->cfg.dry_run) {
+    SampleCfg sc{1.0f / temperature, top_k, (unsigned int)(seed & 0xFFFFFFFFull), (unsigned int)(seed >> 32)};
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->o.state + 64, &sc, sizeof sc, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));        // sc is a stack object
+  }
+  c->sampling = on;
+  return DMTD_OK;
 }
 
 int dmtd_set_n_early(dmtd_ctx* c, int32_t n_early) {

@@ -198,6 +198,102 @@ __global__ void add_embed_rows_kernel(float* __restrict__ h, const WT* __restric
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += Elem<WT>::to_f32(e[k]);
 }
 
+// ---- token selection by sampling: temperature and top-k through the Gumbel-max identity.  The uniforms come
+// ---- from a counter-based SplitMix64 generator keyed by (seed, sequence, position, vocabulary entry), so a draw
+// ---- depends on nothing but those four numbers (graph replays and batch order do not matter).
+
+struct SampleCfg {        // device-resident, written by the host when the setting changes
+  float inv_temp;         // 1 / temperature
+  int top_k;              // <= 0: no restriction
+  unsigned int seed_lo, seed_hi;
+};
+
+__device__ __forceinline__ unsigned long long splitmix_mix(unsigned long long z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// floats in an unsigned order (larger float, larger integer); -0 counts as +0
+__device__ __forceinline__ uint32_t ordered_u32(float v) {
+  const uint32_t u = __float_as_uint(v + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// One block of 1024 threads per sequence, after the LM head: the row at position st->n_tok draws its token from
+// softmax(z / temperature) over the top_k largest logits (logits equal to the k-th largest all stay in).  The
+// k-th largest logit comes from a 4-pass radix select over the ordered bit patterns (integer counts: exact and
+// order independent); the draw is the argmax of z_v / temperature - log(-log(u_v)), u_v the midpoint of one of
+// 2^23 cells of (0, 1) picked by the generator's top 23 bits.  The result replaces the greedy selection keys.
+__global__ void __launch_bounds__(1024) sample_kernel(const float* __restrict__ logits, int V, const SampleCfg* __restrict__ cfg,
+                                                      const DevState* st, unsigned long long* amax, int n_cells, int amax_ld) {
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* z = logits + (size_t)b * V;
+  __shared__ unsigned int hist[256];
+  __shared__ unsigned int sel_prefix, sel_remaining;
+  __shared__ unsigned long long key_w[16];
+  const int top_k = cfg->top_k;
+  const float inv_temp = cfg->inv_temp;
+  uint32_t thr = 0u;                    // entries whose ordered pattern is >= thr stay in
+  if (top_k > 0 && top_k < V) {
+    uint32_t prefix = 0u;
+    unsigned int remaining = (unsigned int)top_k;
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+      if (tid < 256) hist[tid] = 0u;
+      __syncthreads();
+      for (int v = tid; v < V; v += 1024) {
+        const uint32_t o = ordered_u32(z[v]);
+        if ((o & himask) == prefix) atomicAdd(&hist[(o >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        unsigned int above = 0u;
+        int bin = 255;
+        for (; bin > 0; --bin) {
+          if (above + hist[bin] >= remaining) break;
+          above += hist[bin];
+        }
+        sel_prefix = prefix | ((uint32_t)bin << shift);
+        sel_remaining = remaining - above;
+      }
+      __syncthreads();
+      prefix = sel_prefix;
+      remaining = sel_remaining;
+    }
+    thr = prefix;
+  }
+  const unsigned long long seed = ((unsigned long long)cfg->seed_hi << 32) | cfg->seed_lo;
+  const unsigned long long stream = ((unsigned long long)(unsigned int)b << 32) | (unsigned int)st->n_tok;
+  const unsigned long long base = splitmix_mix(splitmix_mix(seed + 0x9E3779B97F4A7C15ull) ^ (stream * 0xD6E8FEB86659FD93ull));
+  unsigned long long key = 0ull;
+  for (int v = tid; v < V; v += 1024) {
+    const float zv = z[v];
+    if (ordered_u32(zv) >= thr) {
+      const unsigned long long r = splitmix_mix(base + (unsigned long long)(v + 1) * 0x9E3779B97F4A7C15ull);
+      const float u = ((float)(r >> 41) + 0.5f) * (1.0f / 8388608.0f);
+      const unsigned long long k = argmax_key(zv * inv_temp - logf(-logf(u)), v);
+      if (k > key) key = k;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long other = __shfl_xor(key, o, 64);
+    if (other > key) key = other;
+  }
+  if (lane == 0) key_w[wave] = key;
+  __syncthreads();
+  if (tid < n_cells) {
+    unsigned long long k = 0ull;
+    if (tid == 0) {
+      k = key_w[0];
+      for (int w = 1; w < 16; ++w) if (key_w[w] > k) k = key_w[w];
+    }
+    amax[(size_t)tid * amax_ld + b] = k;     // cell 0: the draw; the other cells (greedy partial keys): cleared
+  }
+}
+
 // Summands of the next-token loss (Eq. 6) and the greedy choice for the rows of one chunk of a whole-sequence
 // forward: row b*r+i of the launch is position p0+i of sequence b; its target is the sequence's next token
 // (none for the last position n-1: the summand is stored as 0).  nll = log(sum_v exp(z_v - max)) + max - z_target,
