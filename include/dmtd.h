@@ -93,6 +93,16 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
 int dmtd_prefill(dmtd_ctx* ctx, const int32_t* tokens, int32_t batch, int32_t prompt_len,
                  int32_t n_late, int32_t* first_tokens);
 
+/* Prefill for prompts of different lengths (the paper's speed test uses one static length, Sec. 3.4; this is the batch
+ * of its evaluation runs).  tokens: HOST int32 [batch, prompt_len] row-major, sequence b's prompt in its first lengths[b]
+ * entries (the rest is ignored); lengths: HOST int32 [batch], each in [1, prompt_len], the largest equal to prompt_len.
+ * Every sequence's first generated token comes from its own last prompt position, cycles are anchored at the end of
+ * each sequence's own prompt, and all sequences then decode in lockstep (same phase): sequence b's positions trail the
+ * longest sequence's by prompt_len - lengths[b].  dmtd_get_state and max_seq_len refer to the longest sequence;
+ * dmtd_read_kv rows of sequence b are valid up to its own length.  Errors as dmtd_prefill. */
+int dmtd_prefill_ragged(dmtd_ctx* ctx, const int32_t* tokens, int32_t batch, int32_t prompt_len, const int32_t* lengths,
+                        int32_t n_late, int32_t* first_tokens);
+
 /* Run decode steps of cycle length tau with n_late late layers (Sec. 2.2).  If the
  * current cycle is complete (tau tokens emitted, counting the token prefill emitted
  * for cycle 1) the call starts a new cycle with a full step: the pending in-cycle

@@ -54,6 +54,8 @@ def load_library():
     lib.dmtd_create.argtypes = [P(_Config), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, P(C.c_void_p)]
     lib.dmtd_prefill.restype = C.c_int
     lib.dmtd_prefill.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, C.c_int32, C.c_int32, P(C.c_int32)]
+    lib.dmtd_prefill_ragged.restype = C.c_int
+    lib.dmtd_prefill_ragged.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, C.c_int32, P(C.c_int32), C.c_int32, P(C.c_int32)]
     lib.dmtd_decode_cycle.restype = C.c_int
     lib.dmtd_decode_cycle.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
                                       P(C.c_int32), C.c_int32, P(C.c_int32)]
@@ -168,10 +170,17 @@ class Engine:
         except Exception:
             pass
 
-    def prefill(self, tokens, n_late: int = 0) -> np.ndarray:
+    def prefill(self, tokens, n_late: int = 0, lengths=None) -> np.ndarray:
+        """``lengths`` (one per sequence): prompts of different lengths, each in the first entries of its row of ``tokens``."""
         t = np.ascontiguousarray(np.atleast_2d(np.asarray(tokens)), dtype=np.int32)
         first = np.empty(t.shape[0], np.int32)
-        self._check(self.lib.dmtd_prefill(self._h, _i32p(t), t.shape[0], t.shape[1], n_late, _i32p(first)))
+        if lengths is None:
+            self._check(self.lib.dmtd_prefill(self._h, _i32p(t), t.shape[0], t.shape[1], n_late, _i32p(first)))
+        else:
+            ln = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+            if ln.shape != (t.shape[0],):
+                raise ValueError("one length per sequence")
+            self._check(self.lib.dmtd_prefill_ragged(self._h, _i32p(t), t.shape[0], t.shape[1], _i32p(ln), n_late, _i32p(first)))
         self._batch = t.shape[0]
         return first
 

@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
   };
   load_kv(key_begin, min(s_max, key_begin + kps));
 
-  const int pos_first = row_base(st, sel, offset);
+  const int pos_first = row_base(st, sel, offset, b);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
   const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
@@ -326,7 +326,7 @@ __global__ void __launch_bounds__(128) attn_merge_kernel(
 #pragma unroll
   for (int s2 = 0; s2 < PRE; ++s2)
     ov[s2] = (tid < HD && s2 < n_splits) ? part_o[((slot0 + s2) * qv_stride + qv) * HD + tid] : 0.f;
-  const int pos_row = row_base(st, sel, offset) + i;    // row i sees keys 0 .. pos_row
+  const int pos_row = row_base(st, sel, offset, b) + i;    // row i sees keys 0 .. pos_row
   const int n_act = min(n_splits, pos_row / kps + 1);   // ranges that hold keys visible to row i; later ones hold stale partials
   if (tid < ATT_MAX_SPLITS) f_s[tid] = (tid < n_act) ? mv : -INFINITY;
   __syncthreads();

@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const int range_limit = min(s_max, key_begin + kps);
   load_kv(key_begin + 16 * wave, range_limit);
 
-  const int pos_first = row_base(st, sel, offset);
+  const int pos_first = row_base(st, sel, offset, b);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
   const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)

@@ -176,7 +176,7 @@ Ws layout(const dmtd_config& c) {
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
   w.forced = take((size_t)kMaxTau * B * 4);
-  w.state = take(256);
+  w.state = take(kStateDeltaOff + 8 * B);             // counters, sampling parameters, per-sequence position deltas and last prompt positions
   w.inv_freq = take((hd / 2) * 8);
   w.pend_enc = take(B * kMaxTau * d * 4);
   w.enc_tmp = take(rows * d * 4);
@@ -521,16 +521,18 @@ hipError_t add_embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int 
 }
 
 // a8: only each sequence's newest row continues (Sec. 2.2); under the literal Eq. 4 reading its embedding is added
-hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int add_embed, int sel, int offset, int next_layer) {
+// last_pos (prefill of prompts of different lengths): sequence b's row is the one at explicit position last_pos[b]
+hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int add_embed, int sel, int offset, int next_layer,
+                          const int* last_pos = nullptr) {
   const dmtd_config& cf = c->cfg;
   if (c->packed) {
     hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden, add_embed,
                        (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset,
-                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp, (const float*)nullptr);
+                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp, (const float*)nullptr, last_pos);
     dst.n_parts = 1;
   } else {
     hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden,
-                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, (const float*)nullptr);
+                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, (const float*)nullptr, last_pos);
   }
   return hipGetLastError();
 }
@@ -627,7 +629,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
   if (e != hipSuccess) return e;
   if (c->sampling && write_tokens) {
     hipLaunchKernelGGL(sample_kernel, dim3(n_rows), dim3(1024), 0, c->stream, (const float*)(c->ws + c->o.logits), cf.vocab,
-                       (const SampleCfg*)(c->ws + c->o.state + 64), (const DevState*)dev_state(c), amax, AMAX_CELLS, cf.max_batch);
+                       (const SampleCfg*)(c->ws + c->o.state + kStateSampleOff), (const DevState*)dev_state(c), amax, AMAX_CELLS, cf.max_batch);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(n_rows >= 16 ? 1024 : 64 * n_rows), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
@@ -699,11 +701,11 @@ hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
           hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden, 0,
                              (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
                              (const bf16_t*)norm_gain_for_layer(c, F), late.xb, late.xb_lo, late.ssp,
-                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr);
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr);
         else
           hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden,
                              0, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
-                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr);
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         late.n_parts = 1;
       } else {
@@ -774,7 +776,7 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
 }
 
 // Prefill (Sec. 2.2): all prompt positions through all layers, in chunks of rows
-hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
+hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
   const dmtd_config& cf = c->cfg;
   Rows front = front_rows(c), late = late_rows(c);
   const int add_at = cf.full_pos_add_embed ? cf.n_layers - n_late : -1;
@@ -800,8 +802,11 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late) {
       if ((e = run_layer(c, l, front, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
     }
     r_last = r; p_last = p0;
+    // prompts of different lengths: a sequence whose last prompt position lies in this chunk hands that row to the LM head
+    if (ragged && (e = take_last_rows(c, front, late, r, 0, POS_EXPLICIT, p0, cf.n_layers,
+                                      (const int*)(c->ws + c->o.state + kStateDeltaOff) + cf.max_batch)) != hipSuccess) return e;
   }
-  if ((e = take_last_rows(c, front, late, r_last, 0, POS_EXPLICIT, p_last, cf.n_layers)) != hipSuccess) return e;
+  if (!ragged && (e = take_last_rows(c, front, late, r_last, 0, POS_EXPLICIT, p_last, cf.n_layers)) != hipSuccess) return e;
   return run_head(c, late, 1, 1, c->batch);   // state goes from P-1 to n_tok = n_front = P
 }
 
@@ -990,7 +995,7 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
       e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)AMAX_CELLS * cfg->max_batch * 8, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, 256, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, kStateDeltaOff + 8 * (size_t)cfg->max_batch, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
     if (e == hipSuccess && c->packed) {
       // one-time repack of every matrix into MFMA operand order (q, k, v are contiguous: one fused matrix)
@@ -1019,7 +1024,8 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   return DMTD_OK;
 }
 
-int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prompt_len, int32_t n_late, int32_t* first_tokens) {
+static int prefill_impl(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prompt_len, const int32_t* lengths, int32_t n_late,
+                        int32_t* first_tokens) {
   if (!c) return DMTD_EINVAL;
   const dmtd_config& cf = c->cfg;
   if (!tokens) { c->err = "null tokens"; return DMTD_EINVAL; }
@@ -1029,14 +1035,39 @@ int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prom
   if (cf.full_pos_add_embed && c->sched.n_early + n_late > cf.n_layers) { c->err = "n_early + n_late exceeds the number of layers"; return DMTD_EINVAL; }
   if (c->sched.n_tok != 0) { c->err = "already prefilled; call dmtd_reset first"; return DMTD_ESTATE; }
   if (prompt_len >= cf.max_seq_len) { c->err = "prompt does not leave room for a generated token"; return DMTD_ECAPACITY; }
-  for (size_t i = 0; i < (size_t)batch * prompt_len; ++i)
-    if (tokens[i] < 0 || tokens[i] >= cf.vocab) { c->err = "token id outside the vocabulary"; return DMTD_EINVAL; }
+  bool ragged = false;
+  if (lengths) {
+    int longest = 0;
+    for (int b = 0; b < batch; ++b) {
+      if (lengths[b] < 1 || lengths[b] > prompt_len) { c->err = "prompt length outside [1, prompt_len]"; return DMTD_EINVAL; }
+      if (lengths[b] > longest) longest = lengths[b];
+      ragged = ragged || lengths[b] != prompt_len;
+    }
+    if (longest != prompt_len) { c->err = "prompt_len must be the longest prompt's length"; return DMTD_EINVAL; }
+  }
+  for (int b = 0; b < batch; ++b) {
+    const int len = lengths ? lengths[b] : prompt_len;
+    for (int i = 0; i < len; ++i) {
+      const int32_t t = tokens[(size_t)b * prompt_len + i];
+      if (t < 0 || t >= cf.vocab) { c->err = "token id outside the vocabulary"; return DMTD_EINVAL; }
+    }
+  }
   c->batch = batch;
   if (!cf.dry_run) {
     int* dtok = (int*)(c->ws + c->o.tokens);
-    HIP_TRY(c, hipMemcpy2DAsync(dtok, (size_t)cf.max_seq_len * 4, tokens, (size_t)prompt_len * 4, (size_t)prompt_len * 4, batch,
+    // padding behind a shorter prompt is replaced by token 0: those rows run (their results are never read) and must index the table safely
+    std::vector<int32_t> tk(tokens, tokens + (size_t)batch * prompt_len);
+    std::vector<int32_t> meta(2 * (size_t)cf.max_batch, 0);       // delta[max_batch], last_prompt_pos[max_batch]
+    for (int b = 0; b < batch; ++b) {
+      const int len = lengths ? lengths[b] : prompt_len;
+      for (int i = len; i < prompt_len; ++i) tk[(size_t)b * prompt_len + i] = 0;
+      meta[b] = len - prompt_len;
+      meta[cf.max_batch + b] = len - 1;
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->o.state + kStateDeltaOff, meta.data(), meta.size() * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpy2DAsync(dtok, (size_t)cf.max_seq_len * 4, tk.data(), (size_t)prompt_len * 4, (size_t)prompt_len * 4, batch,
                                 hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, enqueue_prefill(c, prompt_len, n_late));
+    HIP_TRY(c, enqueue_prefill(c, prompt_len, n_late, ragged));
     std::vector<int32_t> first(batch);
     HIP_TRY(c, hipMemcpyAsync(first.data(), c->ws + c->o.emitted, (size_t)batch * 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1046,6 +1077,16 @@ int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prom
   }
   c->sched.note_prefill(prompt_len, cf.full_pos_add_embed ? n_late : 0);
   return DMTD_OK;
+}
+
+int dmtd_prefill(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prompt_len, int32_t n_late, int32_t* first_tokens) {
+  return prefill_impl(c, tokens, batch, prompt_len, nullptr, n_late, first_tokens);
+}
+
+int dmtd_prefill_ragged(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32_t prompt_len, const int32_t* lengths, int32_t n_late,
+                        int32_t* first_tokens) {
+  if (c && !lengths) { c->err = "null lengths"; return DMTD_EINVAL; }
+  return prefill_impl(c, tokens, batch, prompt_len, lengths, n_late, first_tokens);
 }
 
 int dmtd_decode_cycle(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new, const int32_t* forced_inputs,
@@ -1286,7 +1327,7 @@ int dmtd_set_sampling(dmtd_ctx* c, float temperature, int32_t top_k, uint64_t se
   const bool on = temperature > 0.f && top_k != 1;      // top_k = 1 is the greedy choice whatever the temperature
   if (on && !c->cfg.dry_run) {
     SampleCfg sc{1.0f / temperature, top_k, (unsigned int)(seed & 0xFFFFFFFFull), (unsigned int)(seed >> 32)};
-    HIP_TRY(c, hipMemcpyAsync(c->ws + c->o.state + 64, &sc, sizeof sc, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->ws + c->o.state + kStateSampleOff, &sc, sizeof sc, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));        // sc is a stack object
   }
   c->sampling = on;
@@ -1310,6 +1351,7 @@ int dmtd_reset(dmtd_ctx* c) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, (DevState*)(c->ws + c->o.state), 0, 0);
     HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemsetAsync(c->ws + c->o.state + kStateDeltaOff, 0, 8 * (size_t)c->cfg.max_batch, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
   }
   c->sched.reset();

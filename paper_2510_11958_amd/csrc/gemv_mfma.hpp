@@ -347,7 +347,7 @@ __global__ void __launch_bounds__(256) embed_pack_kernel(
     int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
     float* __restrict__ ssp) {
   const int row = blockIdx.x, b = row / r, i = row % r;
-  const int pos = row_base(st, sel, offset) + i;
+  const int pos = row_base(st, sel, offset, b) + i;
   const bf16_t* src = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* dst = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = bf16_to_f32(src[k]);
@@ -357,12 +357,15 @@ __global__ void __launch_bounds__(256) embed_pack_kernel(
 __global__ void __launch_bounds__(256) take_last_pack_kernel(
     const float* __restrict__ src, float* dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
     const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset, const bf16_t* __restrict__ gain,
-    bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp, const float* add_rows /* nullable; may be dst */) {
+    bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp, const float* add_rows /* nullable; may be dst */,
+    const int* __restrict__ last_pos /* nullable: sequence b's row is the one at explicit position last_pos[b], if in this launch */) {
   const int b = blockIdx.x;
-  const float* s = src + ((size_t)b * r + (r - 1)) * d;
+  const int i = last_pos ? last_pos[b] - offset : r - 1;
+  if (i < 0 || i >= r) return;
+  const float* s = src + ((size_t)b * r + i) * d;
   float* o = dst + (size_t)b * d;
   const bf16_t* e = nullptr;
-  if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + r - 1] * d;
+  if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset, b) + i] * d;
   const float* ar = add_rows ? add_rows + (size_t)b * d : nullptr;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] = s[k] + (add_embed ? bf16_to_f32(e[k]) : 0.0f) + (ar ? ar[k] : 0.0f);
   pack_row_for_norm(o, gain, d, xb + (size_t)b * d, xb_lo + (size_t)b * d, ssp + b);
@@ -373,7 +376,7 @@ __global__ void __launch_bounds__(256) add_embed_pack_kernel(
     int sel, int offset, int r, int d, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
     float* __restrict__ ssp) {
   const int row = blockIdx.x, b = row / r, i = row % r;
-  const bf16_t* e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset) + i] * d;
+  const bf16_t* e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset, b) + i] * d;
   float* o = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += bf16_to_f32(e[k]);
   pack_row_for_norm(o, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);

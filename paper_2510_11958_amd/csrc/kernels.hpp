@@ -17,20 +17,27 @@ typedef uint16_t bf16_t;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Device-resident scheduler mirror; written only by single-thread kernels.
+// Device-resident scheduler mirror; written only by single-thread kernels.  The counters are those of
+// the longest sequence of the batch; sequence b, whose prompt was shorter by -delta[b] tokens, sits at
+// the same counters plus delta[b] (all zero for prompts of one length).  The block is followed in
+// memory by the sampling parameters (byte 64), delta[max_batch] (byte 128) and last_prompt_pos[max_batch].
 struct DevState {
   int n_tok;         // position of the next token-emitting row
   int n_front;       // first position not yet in the front layers' caches
   int forced_until;  // positions < forced_until hold caller-forced input tokens
   int step_idx;      // step number inside the current decode call
 };
+constexpr int kStateSampleOff = 64, kStateDeltaOff = 128;
+__device__ __forceinline__ const int* seq_delta(const DevState* st) { return (const int*)((const char*)st + kStateDeltaOff); }
 
 // Where a launch's rows sit: row i of sequence b is at position base + offset + i, with
-// base read from the device state (or 0 for POS_EXPLICIT) and offset a launch argument.
+// base read from the device state plus the sequence's delta (or 0 for POS_EXPLICIT: explicit
+// positions are the same for every sequence) and offset a launch argument.
 enum PosSel : int { POS_NTOK = 0, POS_NFRONT = 1, POS_EXPLICIT = 2 };
 
-__device__ __forceinline__ int row_base(const DevState* st, int sel, int offset) {
-  return (sel == POS_NTOK ? st->n_tok : (sel == POS_NFRONT ? st->n_front : 0)) + offset;
+__device__ __forceinline__ int row_base(const DevState* st, int sel, int offset, int b) {
+  if (sel == POS_EXPLICIT) return offset;
+  return (sel == POS_NTOK ? st->n_tok : st->n_front) + seq_delta(st)[b] + offset;
 }
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
@@ -102,7 +109,8 @@ __global__ void begin_call_kernel(DevState* st, int* tokens, int s_max, const in
   const int base = st->n_tok;
   for (int i = threadIdx.x; i < batch * n_forced; i += blockDim.x) {
     const int b = i / n_forced, j = i % n_forced;
-    if (base + j < s_max) tokens[(size_t)b * s_max + base + j] = forced[i];
+    const int pos = base + seq_delta(st)[b] + j;
+    if (pos < s_max) tokens[(size_t)b * s_max + pos] = forced[i];
   }
   __syncthreads();
   if (threadIdx.x == 0) { st->forced_until = base + n_forced; st->step_idx = 0; }
@@ -144,7 +152,8 @@ __global__ void __launch_bounds__(1024) finish_step_kernel(DevState* st, unsigne
     if (lane == 0 && write_tokens) {
       const int tok = argmax_key_index(best);
       emitted[step * batch + b] = tok;
-      if (pos + 1 < s_max && pos + 1 >= forced_until) tokens[(size_t)b * s_max + pos + 1] = tok;
+      const int mine = pos + seq_delta(st)[b];       // this sequence's own position
+      if (mine + 1 < s_max && pos + 1 >= forced_until) tokens[(size_t)b * s_max + mine + 1] = tok;
     }
   }
   __syncthreads();
@@ -161,7 +170,7 @@ template <typename WT>
 __global__ void embed_kernel(const WT* __restrict__ table, const int* __restrict__ tokens, int s_max,
                              const DevState* st, int sel, int explicit_pos, int r, int d, float* __restrict__ h) {
   const int row = blockIdx.x, b = row / r, i = row % r;
-  const int pos = row_base(st, sel, explicit_pos) + i;
+  const int pos = row_base(st, sel, explicit_pos, b) + i;
   const int tok = tokens[(size_t)b * s_max + pos];
   const WT* src = table + (size_t)tok * d;
   float* dst = h + (size_t)row * d;
@@ -171,16 +180,21 @@ __global__ void embed_kernel(const WT* __restrict__ table, const int* __restrict
 // dst[b] = src[b*r + r-1] (+ table[token of that row] under the literal Eq. 4 reading; ExDy variant of that
 // reading: + add_rows[b], the row's encoding output, which may be dst itself): only each sequence's newest
 // row continues into the late layers (Sec. 2.2).
+// With last_pos (prompts of different lengths, explicit positions): sequence b's row is the one at position
+// last_pos[b]; a sequence whose row is not among this launch's r positions is left alone.
 template <typename WT>
 __global__ void take_last_rows_kernel(const float* __restrict__ src, float* dst, int r, int d,
                                       int add_embed, const WT* __restrict__ table, const int* __restrict__ tokens,
-                                      int s_max, const DevState* st, int sel, int explicit_pos, const float* add_rows) {
+                                      int s_max, const DevState* st, int sel, int explicit_pos, const float* add_rows,
+                                      const int* __restrict__ last_pos) {
   const int b = blockIdx.x;
-  const float* s = src + ((size_t)b * r + (r - 1)) * d;
+  const int i = last_pos ? last_pos[b] - explicit_pos : r - 1;
+  if (i < 0 || i >= r) return;
+  const float* s = src + ((size_t)b * r + i) * d;
   float* o = dst + (size_t)b * d;
   const WT* e = nullptr;
   if (add_embed) {
-    const int pos = row_base(st, sel, explicit_pos) + r - 1;
+    const int pos = row_base(st, sel, explicit_pos, b) + i;
     e = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   }
   const float* ar = add_rows ? add_rows + (size_t)b * d : nullptr;
@@ -192,7 +206,7 @@ template <typename WT>
 __global__ void add_embed_rows_kernel(float* __restrict__ h, const WT* __restrict__ table, const int* __restrict__ tokens,
                                       int s_max, const DevState* st, int sel, int explicit_pos, int r, int d) {
   const int row = blockIdx.x, b = row / r, i = row % r;
-  const int pos = row_base(st, sel, explicit_pos) + i;
+  const int pos = row_base(st, sel, explicit_pos, b) + i;
   const WT* e = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* o = h + (size_t)row * d;
   for (int k = threadIdx.x; k < d; k += blockDim.x) o[k] += Elem<WT>::to_f32(e[k]);
@@ -265,7 +279,7 @@ __global__ void __launch_bounds__(1024) sample_kernel(const float* __restrict__ 
     thr = prefix;
   }
   const unsigned long long seed = ((unsigned long long)cfg->seed_hi << 32) | cfg->seed_lo;
-  const unsigned long long stream = ((unsigned long long)(unsigned int)b << 32) | (unsigned int)st->n_tok;
+  const unsigned long long stream = ((unsigned long long)(unsigned int)b << 32) | (unsigned int)(st->n_tok + seq_delta(st)[b]);
   const unsigned long long base = splitmix_mix(splitmix_mix(seed + 0x9E3779B97F4A7C15ull) ^ (stream * 0xD6E8FEB86659FD93ull));
   unsigned long long key = 0ull;
   for (int v = tid; v < V; v += 1024) {

@@ -231,3 +231,16 @@ def test_masked_forward_argument_checks_without_a_gpu():
     with pytest.raises(pkg.DmtdError) as err:
         e.masked_forward(ok_t, ok_m, 1)
     assert err.value.code == pkg.DMTD_ESTATE
+
+
+def test_ragged_prefill_argument_checks_and_schedule_without_a_gpu():
+    e = dry(max_seq_len=32, max_batch=3)
+    toks = np.ones((3, 8), np.int32)
+    for lengths in ([8, 0, 3], [8, 9, 3], [7, 7, 3]):
+        with pytest.raises(pkg.DmtdError) as err:
+            e.prefill(toks, lengths=lengths)
+        assert err.value.code == pkg.DMTD_EINVAL
+    e.prefill(toks, lengths=[8, 2, 5])
+    e.decode_cycle(3, 1)
+    s = e.state()
+    assert (s["n_tok"], s["n_front"], s["phase"]) == (10, 8, 3)     # the longest sequence's counters
