@@ -15,8 +15,8 @@
 // cache.  Scoring: partial dot per lane, summed inside the lane group by shuffles; running softmax
 // with the maximum shared across the wave; p*V accumulated for the 8 output dims a lane owns;
 // lane groups summed by shuffles, the 4 waves through LDS; the range's (max, sum, unnormalised
-// output) go to a partials buffer.  (2) attn_merge_kernel: per (row, KV head, sequence), merges the
-// ranges in order (deterministic) and writes the normalised output; all its loads are issued
+// output) go to a partials buffer.  (2) attn_merge_kernel: per (row, query head, sequence), merges the
+// ranges in a fixed order (deterministic) and writes the normalised output; all its loads are issued
 // before the first one is needed.  The kernel boundary makes the partials visible across the chip
 // (fences and same-kernel grid barriers were measured to cost far more on this chip).
 //
@@ -303,18 +303,25 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
 }
 
 // Merge the ranges' partial results: out[row, head, :] = sum_s f_s o_s / sum_s f_s l_s with
-// f_s = exp(m_s - max_s m_s), ranges taken in order.  One block (128 threads) per (row, query head,
-// sequence); every load is issued before the first one is needed.
+// f_s = exp(m_s - max_s m_s).  One block (256 threads) per (row, query head, sequence): thread (group, d4) takes
+// 4 consecutive d of the ranges group, group + NG, ...; every load is issued before the first one is needed; the
+// maximum and the denominator are wave reductions over one lane per range; the groups' sums are added in group
+// order through LDS (deterministic).
 template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection: high parts to out, low parts to out_lo)
-__global__ void __launch_bounds__(128) attn_merge_kernel(
+__global__ void __launch_bounds__(256) attn_merge_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, OT* __restrict__ out_lo, int ldo,
     int nh, int nkv, int kps, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
-  constexpr int PRE = 32;                 // ranges whose partials a thread fetches before anything is waited for
+  constexpr int T4 = HD / 4;              // threads per group: one per 4 consecutive d
+  constexpr int NG = 256 / T4;            // groups (8 or 16); group sg takes ranges sg, sg + NG, ...
+  constexpr int PRE = 4;                  // ranges per thread fetched before anything is waited for (4 * NG >= 32 ranges)
+  static_assert(ATT_MAX_SPLITS <= 64, "one wave holds a lane per range");
   const int i = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int GQ = nh / nkv, g = head / GQ, j = head % GQ;
-  __shared__ float f_s[ATT_MAX_SPLITS], l_s[ATT_MAX_SPLITS];
-  __shared__ float mm_s, inv_l_s;
+  const int sg = tid / T4, d = (tid % T4) * 4;
+  __shared__ float f_s[ATT_MAX_SPLITS];
+  __shared__ float inv_l_s;
+  __shared__ __attribute__((aligned(16))) float red[NG][HD];
   const size_t slot0 = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
   const size_t qv = (size_t)i * GQ + j;
   float mv = -INFINITY, lv = 0.f;
@@ -322,49 +329,52 @@ __global__ void __launch_bounds__(128) attn_merge_kernel(
     const float* p = part_ml + ((slot0 + tid) * qv_stride + qv) * 2;
     mv = p[0]; lv = p[1];
   }
-  float ov[PRE];
+  const float* po = part_o + ((slot0 + sg) * qv_stride + qv) * HD + d;
+  const size_t po_step = (size_t)NG * qv_stride * HD;
+  f32x4 ov[PRE];
 #pragma unroll
-  for (int s2 = 0; s2 < PRE; ++s2)
-    ov[s2] = (tid < HD && s2 < n_splits) ? part_o[((slot0 + s2) * qv_stride + qv) * HD + tid] : 0.f;
+  for (int u = 0; u < PRE; ++u) {
+    ov[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (sg + u * NG < n_splits) ov[u] = *(const f32x4*)(po + u * po_step);
+  }
   const int pos_row = row_base(st, sel, offset, b) + i;    // row i sees keys 0 .. pos_row
   const int n_act = min(n_splits, pos_row / kps + 1);   // ranges that hold keys visible to row i; later ones hold stale partials
-  if (tid < ATT_MAX_SPLITS) f_s[tid] = (tid < n_act) ? mv : -INFINITY;
-  __syncthreads();
-  if (tid == 0) {
-    float mm = -INFINITY;
-    for (int s2 = 0; s2 < n_act; ++s2) mm = fmaxf(mm, f_s[s2]);
-    mm_s = mm;
-  }
-  __syncthreads();
-  if (tid < ATT_MAX_SPLITS) {
-    const float f = (tid < n_act && mv != -INFINITY) ? __expf(mv - mm_s) : 0.f;
+  if (tid < 64) {
+    // the first wave holds one range per lane: maximum and weighted sum by shuffles (a fixed tree: deterministic)
+    const float m_l = tid < n_act ? mv : -INFINITY;
+    const float mm = wave_max(m_l);
+    const float f = (m_l != -INFINITY) ? __expf(m_l - mm) : 0.f;
     f_s[tid] = f;
-    l_s[tid] = f * lv;
+    const float ll = wave_sum(f == 0.f ? 0.f : f * lv);     // a skipped range may hold anything
+    if (tid == 0) inv_l_s = 1.0f / ll;
   }
   __syncthreads();
-  if (tid == 0) {
-    float ll = 0.f;
-    for (int s2 = 0; s2 < n_act; ++s2) ll += l_s[s2];
-    inv_l_s = 1.0f / ll;
-  }
-  __syncthreads();
-  if (tid < HD) {
-    float o = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s2 = 0; s2 < PRE; ++s2) {
-      const float f = s2 < n_act ? f_s[s2] : 0.f;
-      o += (f == 0.f) ? 0.f : f * ov[s2];
+  for (int u = 0; u < PRE; ++u) {
+    const int s2 = sg + u * NG;
+    const float f = s2 < n_act ? f_s[s2] : 0.f;
+    if (f != 0.f) o += f * ov[u];
+  }
+  for (int s2 = sg + PRE * NG; s2 < n_act; s2 += NG) {
+    const float f = f_s[s2];
+    if (f != 0.f) o += f * *(const f32x4*)(po + (size_t)(s2 / NG) * po_step);
+  }
+  *(f32x4*)&red[sg][d] = o;
+  __syncthreads();
+  if (tid < T4) {
+    f32x4 t = *(const f32x4*)&red[0][d];
+#pragma unroll
+    for (int q = 1; q < NG; ++q) t += *(const f32x4*)&red[q][d];
+    const size_t at = (size_t)(b * r_total + i) * ldo + (size_t)head * HD + d;
+    const float inv_l = inv_l_s;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float res = t[e] * inv_l;
+      const OT hi = Elem<OT>::from_f32(res);
+      out[at + e] = hi;
+      if (out_lo) out_lo[at + e] = Elem<OT>::from_f32(res - Elem<OT>::to_f32(hi));
     }
-    for (int s2 = PRE; s2 < n_act; ++s2) {
-      const float f = f_s[s2];
-      const float v = part_o[((slot0 + s2) * qv_stride + qv) * HD + tid];
-      o += (f == 0.f) ? 0.f : f * v;
-    }
-    const size_t at = (size_t)(b * r_total + i) * ldo + (size_t)head * HD + tid;
-    const float res = o * inv_l_s;
-    const OT hi = Elem<OT>::from_f32(res);
-    out[at] = hi;
-    if (out_lo) out_lo[at] = Elem<OT>::from_f32(res - Elem<OT>::to_f32(hi));
   }
 }
 

@@ -27,6 +27,140 @@
 
 namespace dmtd {
 
+// Sum over the 16 lanes of a DPP row by rotations (every lane ends up with the total).
+template <int N>
+__device__ __forceinline__ float row_ror_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += row_ror_f32<8>(v);
+  v += row_ror_f32<4>(v);
+  v += row_ror_f32<2>(v);
+  v += row_ror_f32<1>(v);
+  return v;
+}
+
+constexpr int ATT_QPAD = 8;     // bf16 elements of padding per LDS query row
+
+// A vector of the prologue is handled by the 16 lanes of a DPP row; lane l holds the rotary pairs
+// (HL*l + e, HD/2 + HL*l + e), e < HL = HD/32, as two short vectors.
+template <int HD> struct AttRowLane {
+  static constexpr int HL = HD / 32;
+  typedef float fvec_t __attribute__((ext_vector_type(HD / 32)));
+  typedef unsigned short hvec_t __attribute__((ext_vector_type(HD / 32)));
+};
+// The block's query vector of row group lane group grp (if any): loaded before the positions are known.
+template <int HD> struct AttQueryPre {
+  typename AttRowLane<HD>::fvec_t xa, xb;
+  typename AttRowLane<HD>::hvec_t g0, g1;
+};
+template <int HD>
+__device__ __forceinline__ AttQueryPre<HD> attn_preload_query(const float* __restrict__ qkv, int ldq, const bf16_t* __restrict__ q_gain,
+                                                              int b, int g, int GQ, int r_total, int row0, int QV, int tid) {
+  typedef typename AttRowLane<HD>::fvec_t fvec_t;
+  typedef typename AttRowLane<HD>::hvec_t hvec_t;
+  constexpr int HL = AttRowLane<HD>::HL, half = HD / 2;
+  const int l = tid & 15, v = tid >> 4;
+  AttQueryPre<HD> p;
+#pragma unroll
+  for (int e = 0; e < HL; ++e) { p.xa[e] = 0.f; p.xb[e] = 0.f; p.g0[e] = 0; p.g1[e] = 0; }
+  if (v < QV) {
+    const float* src = qkv + (size_t)(b * r_total + row0 + v / GQ) * ldq + (size_t)(g * GQ + v % GQ) * HD + HL * l;
+    p.xa = *(const fvec_t*)src; p.xb = *(const fvec_t*)(src + half);
+    p.g0 = *(const hvec_t*)(q_gain + HL * l); p.g1 = *(const hvec_t*)(q_gain + half + HL * l);
+  }
+  return p;
+}
+
+// Prologue of the matrix-core kernel: per-head RMSNorm + RoPE (pair (i, i + HD/2), cos/sin from the table) of the
+// block's QV query vectors, scaled by 1/sqrt(HD) and written to LDS as the B operands of the score MFMAs (bf16 high
+// and low parts, a lane's 8 consecutive d are one 16-byte read); and, if the block's key range holds new positions,
+// of the launch's first n_new keys and values into knew_s / vnew_s, rounded to the cache's type (the writer block
+// also stores them to the cache).  A vector is handled by the 16 lanes of a DPP row, each with HD/32 rotary pairs
+// loaded as vectors, so the block's 16 rows take 16 vectors at a time and the sum of squares needs no LDS traffic.
+template <int HD>
+__device__ __forceinline__ void attn_prepare_rows_mfma(
+    const float* __restrict__ qkv, int ldq, const bf16_t* __restrict__ q_gain, const bf16_t* __restrict__ k_gain,
+    const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int b, int g, int nh, int nkv, int s_max,
+    float eps, int r_total, int row0, int QV, int n_new, bool holds_new, bool writer, int pos_first, int key_begin, int key_end,
+    bf16_t (*qhi_s)[HD + ATT_QPAD], bf16_t (*qlo_s)[HD + ATT_QPAD], float (*knew_s)[HD], float (*vnew_s)[HD], int tid,
+    const AttQueryPre<HD>& pre) {
+  constexpr int half = HD / 2;
+  constexpr int HL = AttRowLane<HD>::HL;     // rotary pairs per lane (4 or 2): elements HL*l .. and half + HL*l ..
+  typedef typename AttRowLane<HD>::fvec_t fvec_t;
+  typedef typename AttRowLane<HD>::hvec_t hvec_t;
+  const int GQ = nh / nkv;
+  const float scale = rsqrtf((float)HD);
+  const int l = tid & 15, grp = tid >> 4;    // lane of the row; row of the block (0 .. 15)
+  const int n_vec = QV + (holds_new ? 2 * n_new : 0);         // queries, new keys, new values
+  for (int v = grp; v < n_vec; v += 16) {
+    const bool is_q = v < QV, is_k = !is_q && v < QV + n_new;
+    const int row = is_q ? row0 + v / GQ : (is_k ? v - QV : v - QV - n_new);       // row of the launch
+    const int hcol = is_q ? g * GQ + v % GQ : (is_k ? nh + g : nh + nkv + g);
+    const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD + HL * l;
+    fvec_t xa = pre.xa, xb = pre.xb;          // queries (all in the first round) were fetched at kernel entry
+    if (!is_q) { xa = *(const fvec_t*)src; xb = *(const fvec_t*)(src + half); }
+    float x0[HL], x1[HL];
+#pragma unroll
+    for (int e = 0; e < HL; ++e) { x0[e] = xa[e]; x1[e] = xb[e]; }
+    if (!is_q && !is_k) {
+      // a value vector: rounded to the cache type, kept for this launch's scores, stored by the writer
+      const int key = pos_first + row;
+      const bool wr = writer && key >= key_begin && key < key_end;
+      bf16_t* dst = vc + (((size_t)b * nkv + g) * s_max + key) * HD + HL * l;
+      hvec_t c0, c1;
+#pragma unroll
+      for (int e = 0; e < HL; ++e) {
+        c0[e] = f32_to_bf16(x0[e]); c1[e] = f32_to_bf16(x1[e]);
+        vnew_s[row][HL * l + e] = bf16_to_f32(c0[e]); vnew_s[row][half + HL * l + e] = bf16_to_f32(c1[e]);
+      }
+      if (wr) { *(hvec_t*)dst = c0; *(hvec_t*)(dst + half) = c1; }
+      continue;
+    }
+    hvec_t g0 = pre.g0, g1 = pre.g1;
+    if (!is_q) { g0 = *(const hvec_t*)(k_gain + HL * l); g1 = *(const hvec_t*)(k_gain + half + HL * l); }
+    const float2* rp = rope_tab + (size_t)(pos_first + row) * half + HL * l;
+    float2 cs[HL];
+#pragma unroll
+    for (int e = 0; e < HL; ++e) cs[e] = rp[e];
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < HL; ++e) ss += x0[e] * x0[e] + x1[e] * x1[e];
+    const float rs = rsqrtf(row16_sum(ss) / (float)HD + eps);
+    float y0[HL], y1[HL];
+#pragma unroll
+    for (int e = 0; e < HL; ++e) {
+      const float a0 = x0[e] * (rs * bf16_to_f32(g0[e])), a1 = x1[e] * (rs * bf16_to_f32(g1[e]));
+      y0[e] = a0 * cs[e].x - a1 * cs[e].y;
+      y1[e] = a1 * cs[e].x + a0 * cs[e].y;
+    }
+    if (is_q) {
+      hvec_t h0, h1, l0, l1;
+#pragma unroll
+      for (int e = 0; e < HL; ++e) {
+        const float q0 = y0[e] * scale, q1 = y1[e] * scale;
+        bf16_t hh, ll;
+        split_bf16(q0, hh, ll); h0[e] = hh; l0[e] = ll;
+        split_bf16(q1, hh, ll); h1[e] = hh; l1[e] = ll;
+      }
+      *(hvec_t*)&qhi_s[v][HL * l] = h0; *(hvec_t*)&qhi_s[v][half + HL * l] = h1;
+      *(hvec_t*)&qlo_s[v][HL * l] = l0; *(hvec_t*)&qlo_s[v][half + HL * l] = l1;
+    } else {
+      const int key = pos_first + row;
+      hvec_t c0, c1;
+#pragma unroll
+      for (int e = 0; e < HL; ++e) {
+        c0[e] = f32_to_bf16(y0[e]); c1[e] = f32_to_bf16(y1[e]);
+        knew_s[row][HL * l + e] = bf16_to_f32(c0[e]); knew_s[row][half + HL * l + e] = bf16_to_f32(c1[e]);
+      }
+      if (writer && key >= key_begin && key < key_end) {
+        bf16_t* dst = kc + (((size_t)b * nkv + g) * s_max + key) * HD + HL * l;
+        *(hvec_t*)dst = c0; *(hvec_t*)(dst + half) = c1;
+      }
+    }
+  }
+}
+
 template <int HD>
 __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
     const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
@@ -50,9 +184,9 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const int key_begin = split * kps;
   const int sl = lane & 15, kq = lane >> 4;
 
-  __shared__ float q_s[QVT][HD];
-  __shared__ float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
-  __shared__ float wacc[4][QVT][HD];
+  __shared__ __attribute__((aligned(16))) bf16_t qhi_s[QVT][HD + ATT_QPAD], qlo_s[QVT][HD + ATT_QPAD];
+  __shared__ __attribute__((aligned(16))) float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
+  __shared__ __attribute__((aligned(16))) float wacc[4][QVT][HD];
   __shared__ float wm[4][QVT], wl[4][QVT];
 
   const bf16_t* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD;
@@ -77,6 +211,9 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const int range_limit = min(s_max, key_begin + kps);
   load_kv(key_begin + 16 * wave, range_limit);
 
+  // the block's query vectors do not depend on the positions: fetched now, next to K and V
+  const AttQueryPre<HD> qpre = attn_preload_query<HD>(qkv, ldq, (const bf16_t*)q_gain, b, g, GQ, r_total, rg * rpb, QV, tid);
+
   const int pos_first = row_base(st, sel, offset, b);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
   const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
@@ -86,31 +223,27 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const bool holds_new = key_end > pos_first;
   const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
 
-  attn_prepare_rows<bf16_t, HD>(qkv, ldq, q_gain, k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total, rg * rpb, QV, n_new, holds_new,
-                                writer, pos_first, key_begin, key_end, q_s, knew_s, vnew_s, lane, wave);
+  attn_prepare_rows_mfma<HD>(qkv, ldq, (const bf16_t*)q_gain, (const bf16_t*)k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total,
+                             rg * rpb, QV, n_new, holds_new, writer, pos_first, key_begin, key_end, qhi_s, qlo_s, knew_s, vnew_s, tid, qpre);
   __syncthreads();
 
   // queries as B operands: lane (q = sl, d group kq), high and low bf16 parts
   bf16x8_t qhi[KSTEPS], qlo[KSTEPS];
 #pragma unroll
   for (int t = 0; t < KSTEPS; ++t) {
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float x0 = sl < QV ? q_s[sl][32 * t + 8 * kq + 2 * e] : 0.f, x1 = sl < QV ? q_s[sl][32 * t + 8 * kq + 2 * e + 1] : 0.f;
-      const uint32_t h = pack_bf16x2(x0, x1);
-      hi[e] = h;
-      lo[e] = pack_bf16x2(x0 - __uint_as_float(h << 16), x1 - __uint_as_float(h & 0xFFFF0000u));
+    u32x4 h = {0, 0, 0, 0}, lo = h;
+    if (sl < QV) {
+      h = *(const u32x4*)&qhi_s[sl][32 * t + 8 * kq];
+      lo = *(const u32x4*)&qlo_s[sl][32 * t + 8 * kq];
     }
-    qhi[t] = __builtin_bit_cast(bf16x8_t, u32x4{hi[0], hi[1], hi[2], hi[3]});
-    qlo[t] = __builtin_bit_cast(bf16x8_t, u32x4{lo[0], lo[1], lo[2], lo[3]});
+    qhi[t] = __builtin_bit_cast(bf16x8_t, h);
+    qlo[t] = __builtin_bit_cast(bf16x8_t, lo);
   }
   const int my_row_pos = pos0 + sl / GQ;                   // query sl belongs to row sl / GQ: it sees keys <= this position
   float m_run = -INFINITY, l_run = 0.f;
   f32x4 acc[DPL];
 #pragma unroll
   for (int e = 0; e < DPL; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-
   for (int it0 = key_begin; it0 < key_end; it0 += 64) {
     const int base = it0 + 16 * wave;                           // this wave's 16 keys
     u32x4 ka[KSTEPS];
@@ -186,7 +319,6 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
 #pragma unroll
       for (int e = 0; e < DPL; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[m], vf[m][e], acc[e], 0, 0, 0);
   }
-
   // per-wave totals: l summed over the 4 kq lanes of a query
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
@@ -203,17 +335,19 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
   float* my_o = part_o + slot * HD;
   float* my_ml = part_ml + slot * 2;
-  for (int e = tid; e < QV * HD; e += 256) {
-    const int qv = e / HD, d = e % HD;
+  // the 4 waves' partials of a query vector, 4 consecutive d per thread
+  for (int e = tid; e < QV * (HD / 4); e += 256) {
+    const int qv = e / (HD / 4), d = (e % (HD / 4)) * 4;
     const float mm = fmaxf(fmaxf(wm[0][qv], wm[1][qv]), fmaxf(wm[2][qv], wm[3][qv]));
-    float o = 0.f, ll = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    float ll = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
-      o += f * wacc[w][qv][d];
+      o += f * *(const f32x4*)&wacc[w][qv][d];
       ll += f * wl[w][qv];
     }
-    my_o[qv * HD + d] = o;
+    *(f32x4*)(my_o + qv * HD + d) = o;
     if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
   }
 }

@@ -427,7 +427,7 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn
   hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
                      cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
-  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, attn_lo, qd,
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
 }
 
@@ -454,7 +454,7 @@ void launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT*
   hipLaunchKernelGGL((attn_split_mfma_kernel<HD>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
                      cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
-  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(128), 0, c->stream, po, pml, attn, attn_lo, qd,
+  hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
 }
 

@@ -174,6 +174,25 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   }
   for (int c = tid + NBST * NT; c < 2 * n_chunks; c += NT) *chunk_dst(c) = *chunk_src(c);   // beyond what the early loads covered
   __syncthreads();
+  if (NORM) {
+    // the rows' 1/rms while the weights are still on their way: per column, 16 threads sum interleaved parts, then
+    // one thread sums the 16 (fixed order: deterministic); the epilogue's barrier makes rs_s visible
+    for (int t = tid; t < 256; t += NT) {
+      const int c = t >> 4, j = t & 15;
+      float s = 0.f;
+      if (c < M) {
+        for (int p = j; p < a.n_parts; p += 16) s += ss_items[p * M + c];
+      }
+      ss_s[c][j] = s;
+    }
+    __syncthreads();
+    if (tid < 16) {
+      float s = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += ss_s[tid][j];
+      rs_s[tid] = rsqrtf(s / (float)K + a.eps);
+    }
+  }
 
   for (int base = s0; base < s1; base += PF) {           // one round unless the wave's k-range exceeds PF steps
     if (!ROLL && base != s0) load_a(base);
@@ -252,26 +271,6 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   }
   if (EPI == EPI_LOGITS && tid < 16) key_s[tid] = 0ull;
   __syncthreads();
-  if (NORM) {
-    // per column: 16 threads sum interleaved parts, then one thread sums the 16 (fixed order: deterministic)
-    for (int t = tid; t < 256; t += NT) {
-      const int c = t >> 4, j = t & 15;
-      float s = 0.f;
-      if (c < M) {
-        for (int p = j; p < a.n_parts; p += 16) s += ss_items[p * M + c];
-      }
-      ss_s[c][j] = s;
-    }
-    __syncthreads();
-    if (tid < 16) {
-      float s = 0.f;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) s += ss_s[tid][j];
-      rs_s[tid] = rsqrtf(s / (float)K + a.eps);
-    }
-    __syncthreads();
-  }
-
 #pragma unroll
   for (int q = 0; q < EPN; ++q) {
     const int t = tid + q * NT;
@@ -300,15 +299,13 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
         if (EPI == EPI_LOGITS) atomicMax(&key_s[c], argmax_key(v0, n));
       }
     }
-    if (EPI == EPI_RESID) ss_s[c][row] = hsq;
-  }
-  if (EPI == EPI_RESID) {
-    __syncthreads();
-    if (tid < M) {
-      float s = 0.f;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) s += ss_s[tid][j];
-      a.ssp_next[(size_t)tile * a.ssp_ld + tid] = s;
+    if (EPI == EPI_RESID) {
+      // sum of squares of the tile's 16 outputs of column c: its 16 neighbouring lanes (inactive ones hold 0)
+      hsq += __shfl_xor(hsq, 1, 64);
+      hsq += __shfl_xor(hsq, 2, 64);
+      hsq += __shfl_xor(hsq, 4, 64);
+      hsq += __shfl_xor(hsq, 8, 64);
+      if (row == 0 && c < M) a.ssp_next[(size_t)tile * a.ssp_ld + c] = hsq;
     }
   }
   if (EPI == EPI_LOGITS) {
