@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
@@ -11,7 +12,26 @@ HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading scalar kernel arguments arrive in SGPRs at wave launch instead of through a first dependent load
+    # (the latency-bound attention kernels start ~0.2 us earlier; by-value argument structs are not covered)
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
+    # per-kernel register and scratch figures on stderr: build_library() refuses a build whose matrix-core kernels spill
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+
+def spilling_mfma_kernels(remarks: str) -> list:
+    """Names of the *_mfma_kernel instantiations whose resource-usage remarks report a scratch size above zero."""
+    bad, name = [], None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name and "_mfma_kernel" in name and int(m.group(1)) > 0:
+            bad.append(f"{name} ({m.group(1)} bytes/lane)")
+    return bad
 
 
 def build_library(verbose: bool = False) -> str:
@@ -20,6 +40,10 @@ def build_library(verbose: bool = False) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stderr)
+    spilled = spilling_mfma_kernels(res.stderr)
+    if spilled:
+        # a weight-streaming kernel that spills to scratch still computes the right values, several times slower
+        raise RuntimeError("matrix-core kernels use scratch memory (register spills): " + ", ".join(spilled))
     if verbose:
         print(" ".join(cmd))
     return LIB_PATH

@@ -37,7 +37,8 @@ constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA
 // Waves that split K for one matrix (NW) and k-steps a wave keeps in flight as a rolling window (PF), per projection;
 // NW = 0: the one-round rule of launch_mfma with kMfmaPF.  Defaults from sweeps at 4B shapes on MI355X (us per launch,
 // 3 rows, against the one-round rule): gate/up 20.0 (20.5), down 12.7 (14.3), O 8.2 (8.4), LM head 111.7 (136.7);
-// rolling windows did not help the QKV projection.  The macros exist so a sweep can override them at build time.
+// rolling windows did not help the QKV projection.  O shares down's instantiation (PF 5: its 4 k-steps per wave at 4B
+// shapes plus one empty slot; the PF 4 instantiation spilled registers).  The macros exist so a sweep can override them at build time.
 #ifndef DMTD_GU_NW
 #define DMTD_GU_NW 4
 #define DMTD_GU_PF 4
@@ -48,7 +49,7 @@ constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA
 #endif
 #ifndef DMTD_O_NW
 #define DMTD_O_NW 16
-#define DMTD_O_PF 4
+#define DMTD_O_PF 5
 #endif
 #ifndef DMTD_LM_NW
 #define DMTD_LM_NW 5
@@ -362,7 +363,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
         if (ae != hipSuccess) return ae;                                                                                  \
         big_lds = true;                                                                                                   \
       }                                                                                                                   \
-      hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g);                                                 \
+      hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g);        \
     } while (0)
     if constexpr (ROLL_NW > 0) DMTD_LAUNCH_MFMA(ROLL_NW * MATS);
     else if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);

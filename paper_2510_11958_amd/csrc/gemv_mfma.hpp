@@ -92,8 +92,12 @@ struct MfmaArgs {
 // memory, 2 * M * K * 2 bytes, plus M * n_parts * 4 for the partial sums of squares if NORM) and the
 // waves take their B operands from there; the host sends rows
 // that do not fit there to the LDS-tiled kernel (gemm_mfma.hpp).
+// The arguments every wave needs before it can issue its first loads are passed as scalars ahead of the struct: the
+// leading scalar arguments of a kernel arrive in registers at wave launch, the struct through a load.
 template <int EPI, bool NORM, int PF, int NWT, bool ROLL = false>   // NWT: waves per block (all matrices)
-__global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
+__global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, const bf16_t* W2_,
+                                                             const bf16_t* xb_, const bf16_t* xb_lo_,
+                                                             int M_, int N_, int K_, MfmaArgs a) {
   extern __shared__ float4 dyn_smem[];
   bf16_t* xs = (bf16_t*)dyn_smem;                        // [2 planes][M][K], then (NORM) M * n_parts floats
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -101,18 +105,18 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   static_assert(nw >= 1 && nw <= MFMA_MAX_WAVES, "waves per tile");
   __shared__ float red[MATS][nw][16][17];               // [matrix][wave][column][row], padded
   __shared__ float ss_s[16][17];
-  float* ss_items = (float*)(xs + (size_t)2 * a.M * a.K);   // NORM: the producer's partial sums [n_parts][M], behind the rows
+  float* ss_items = (float*)(xs + (size_t)2 * M_ * K_);   // NORM: the producer's partial sums [n_parts][M], behind the rows
   __shared__ float rs_s[16];
   __shared__ unsigned long long key_s[16];
   const int tid = threadIdx.x, lane = tid & 63, wall = tid >> 6;
   const int mat = wall / nw, w = wall % nw;
   const int r = lane & 15, kg = lane >> 4;     // B and D: column r
-  const int K = a.K, N = a.N, M = a.M;
+  const int K = K_, N = N_, M = M_;
   const int tile = blockIdx.x;
   const int KS = K >> 6;                       // k-steps of 64 elements
   const int s0 = (int)((long)w * KS / nw), s1 = (int)((long)(w + 1) * KS / nw);
 
-  const bf16_t* __restrict__ abase = (mat == 0 ? a.W : a.W2) + ((size_t)tile * KS) * 1024 + lane * 8;
+  const bf16_t* __restrict__ abase = (mat == 0 ? W_ : W2_) + ((size_t)tile * KS) * 1024 + lane * 8;
   const bool colact = r < M;
   const int ldxs = K;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = acc;
@@ -128,7 +132,7 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   // plane behind the high one, so a 16-byte chunk's source and destination are linear in its index
   const int n_chunks = M * (K >> 3);                // 16-byte chunks per plane
   auto chunk_src = [&](int c) {
-    return (const u32x4*)(c >= n_chunks ? a.xb_lo + (size_t)(c - n_chunks) * 8 : a.xb + (size_t)c * 8);
+    return (const u32x4*)(c >= n_chunks ? xb_lo_ + (size_t)(c - n_chunks) * 8 : xb_ + (size_t)c * 8);
   };
   auto chunk_dst = [&](int c) { return (u32x4*)(xs + (size_t)c * 8); };
 #pragma unroll
@@ -164,8 +168,10 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(MfmaArgs a) {
   }
   if (NORM) {
     // the producer's partial sums of squares, M * n_parts floats, fetched by all threads while the weights fly
-    const int n_items = M * a.n_parts;
-    for (int i = tid; i < n_items; i += NT) ss_items[i] = a.ssp[(size_t)(i / M) * a.ssp_ld + (i % M)];
+    for (int p = tid >> 4; p < a.n_parts; p += NT / 16) {
+      const int m = tid & 15;
+      if (m < M) ss_items[p * M + m] = a.ssp[(size_t)p * a.ssp_ld + m];
+    }
   }
 #pragma unroll
   for (int j = 0; j < NBST; ++j) {

@@ -244,3 +244,20 @@ def test_ragged_prefill_argument_checks_and_schedule_without_a_gpu():
     e.decode_cycle(3, 1)
     s = e.state()
     assert (s["n_tok"], s["n_front"], s["phase"]) == (10, 8, 3)     # the longest sequence's counters
+
+
+def test_build_refuses_spilling_matrix_core_kernels():
+    """build_library() reads the compiler's resource-usage remarks: a *_mfma_kernel with scratch is reported, others are not."""
+    from paper_2510_11958_amd.build import spilling_mfma_kernels
+    remarks = "\n".join([
+        "x.hip:1:1: remark: Function Name: _ZN4dmtd16gemv_mfma_kernelILi1ELb0ELi4ELi16ELb1EEEv [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     VGPRs: 128 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 516 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:2:1: remark: Function Name: _ZN4dmtd16gemv_rows_kernelIfLi1EEEv [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:2:1: remark:     ScratchSize [bytes/lane]: 32 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:3:1: remark: Function Name: _ZN4dmtd22attn_split_mfma_kernelILi128EEEv [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:3:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    bad = spilling_mfma_kernels(remarks)
+    assert len(bad) == 1 and "gemv_mfma_kernel" in bad[0] and "516" in bad[0]
+    assert spilling_mfma_kernels("") == []
