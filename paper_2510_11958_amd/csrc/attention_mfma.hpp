@@ -84,7 +84,7 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
     const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int b, int g, int nh, int nkv, int s_max,
     float eps, int r_total, int row0, int QV, int n_new, bool holds_new, bool writer, int pos_first, int key_begin, int key_end,
     bf16_t (*qhi_s)[HD + ATT_QPAD], bf16_t (*qlo_s)[HD + ATT_QPAD], float (*knew_s)[HD], float (*vnew_s)[HD], int tid,
-    const AttQueryPre<HD>& pre) {
+    int n_groups /* 16-lane rows in the block */, const AttQueryPre<HD>& pre) {
   constexpr int half = HD / 2;
   constexpr int HL = AttRowLane<HD>::HL;     // rotary pairs per lane (4 or 2): elements HL*l .. and half + HL*l ..
   typedef typename AttRowLane<HD>::fvec_t fvec_t;
@@ -93,12 +93,12 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
   const float scale = rsqrtf((float)HD);
   const int l = tid & 15, grp = tid >> 4;    // lane of the row; row of the block (0 .. 15)
   const int n_vec = QV + (holds_new ? 2 * n_new : 0);         // queries, new keys, new values
-  for (int v = grp; v < n_vec; v += 16) {
+  for (int v = grp; v < n_vec; v += n_groups) {
     const bool is_q = v < QV, is_k = !is_q && v < QV + n_new;
     const int row = is_q ? row0 + v / GQ : (is_k ? v - QV : v - QV - n_new);       // row of the launch
     const int hcol = is_q ? g * GQ + v % GQ : (is_k ? nh + g : nh + nkv + g);
     const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD + HL * l;
-    fvec_t xa = pre.xa, xb = pre.xb;          // queries (all in the first round) were fetched at kernel entry
+    fvec_t xa = pre.xa, xb = pre.xb;          // queries (all in the first round: QV <= 16 <= n_groups) were fetched at kernel entry
     if (!is_q) { xa = *(const fvec_t*)src; xb = *(const fvec_t*)(src + half); }
     float x0[HL], x1[HL];
 #pragma unroll
@@ -161,14 +161,20 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
   }
 }
 
-template <int HD>
-__global__ void __launch_bounds__(256) attn_split_mfma_kernel(
+// NW waves per block take interleaved groups of 16 keys.  FINAL: the launch has ONE key range per (row group, KV head,
+// sequence), so the block's result is the attention output itself: it is normalised and written as the packed input
+// of the O projection (high parts to out, low parts to out_lo) and no merge kernel follows.  The waves' partial
+// results meet in dynamic shared memory: NW * QV * HD floats (QV = the block's query vectors).
+template <int HD, int NW, bool FINAL>
+__global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
     const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
     const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
     float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
-    int kps /* keys per range, a multiple of 64 */, int n_splits, int qv_stride,
-    const DevState* st, int sel, int offset, int r_total, int do_append) {
+    int kps /* keys per range, a multiple of 16 * NW */, int n_splits, int qv_stride,
+    const DevState* st, int sel, int offset, int r_total, int do_append,
+    bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int ldo /* FINAL only */) {
   constexpr int QVT = 16;
+  constexpr int NT = 64 * NW;
   constexpr int KSTEPS = HD / 32;      // MFMA steps over d for the scores
   constexpr int DPL = HD / 16;         // output dims per lane (8 or 4)
   constexpr int NEW_MAX = 16;
@@ -186,8 +192,9 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
 
   __shared__ __attribute__((aligned(16))) bf16_t qhi_s[QVT][HD + ATT_QPAD], qlo_s[QVT][HD + ATT_QPAD];
   __shared__ __attribute__((aligned(16))) float knew_s[NEW_MAX][HD], vnew_s[NEW_MAX][HD];
-  __shared__ __attribute__((aligned(16))) float wacc[4][QVT][HD];
-  __shared__ float wm[4][QVT], wl[4][QVT];
+  extern __shared__ float4 att_dyn_smem[];
+  float* wacc = (float*)att_dyn_smem;                          // [NW][QV][HD]
+  __shared__ float wm[NW][QVT], wl[NW][QVT];
 
   const bf16_t* kbase = kc + (((size_t)b * nkv + g) * s_max) * HD;
   const bf16_t* vbase = vc + (((size_t)b * nkv + g) * s_max) * HD;
@@ -224,7 +231,7 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
 
   attn_prepare_rows_mfma<HD>(qkv, ldq, (const bf16_t*)q_gain, (const bf16_t*)k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total,
-                             rg * rpb, QV, n_new, holds_new, writer, pos_first, key_begin, key_end, qhi_s, qlo_s, knew_s, vnew_s, tid, qpre);
+                             rg * rpb, QV, n_new, holds_new, writer, pos_first, key_begin, key_end, qhi_s, qlo_s, knew_s, vnew_s, tid, NT / 16, qpre);
   __syncthreads();
 
   // queries as B operands: lane (q = sl, d group kq), high and low bf16 parts
@@ -244,7 +251,7 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   f32x4 acc[DPL];
 #pragma unroll
   for (int e = 0; e < DPL; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int it0 = key_begin; it0 < key_end; it0 += 64) {
+  for (int it0 = key_begin; it0 < key_end; it0 += 16 * NW) {
     const int base = it0 + 16 * wave;                           // this wave's 16 keys
     u32x4 ka[KSTEPS];
     float vf[4][DPL];
@@ -257,7 +264,7 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
         vf[m][2 * e] = __uint_as_float(vr[m][e] << 16);
         vf[m][2 * e + 1] = __uint_as_float(vr[m][e] & 0xFFFF0000u);
       }
-    if (it0 + 64 < key_end) load_kv(base + 64, key_end);        // the next iteration's keys fly during this one
+    if (it0 + 16 * NW < key_end) load_kv(base + 16 * NW, key_end);   // the next iteration's keys fly during this one
     if (holds_new) {
       // new positions: key and value come from LDS (the cache slot is written by this launch, maybe not yet)
       const int ik = base + sl - pos_first;
@@ -327,28 +334,42 @@ __global__ void __launch_bounds__(256) attn_split_mfma_kernel(
   for (int j = 0; j < 4; ++j) {
     const int qv = 4 * kq + j;
     if (qv < QV) {
+      float* dst = wacc + ((size_t)wave * QV + qv) * HD + DPL * sl;
 #pragma unroll
-      for (int e = 0; e < DPL; ++e) wacc[wave][qv][DPL * sl + e] = acc[e][j];
+      for (int e = 0; e < DPL; ++e) dst[e] = acc[e][j];
     }
   }
   __syncthreads();
   const size_t slot = (((size_t)b * nkv + g) * ATT_MAX_SPLITS + split) * qv_stride + (size_t)rg * rpb * GQ;
   float* my_o = part_o + slot * HD;
   float* my_ml = part_ml + slot * 2;
-  // the 4 waves' partials of a query vector, 4 consecutive d per thread
-  for (int e = tid; e < QV * (HD / 4); e += 256) {
+  // the waves' partials of a query vector, 4 consecutive d per thread
+  for (int e = tid; e < QV * (HD / 4); e += NT) {
     const int qv = e / (HD / 4), d = (e % (HD / 4)) * 4;
-    const float mm = fmaxf(fmaxf(wm[0][qv], wm[1][qv]), fmaxf(wm[2][qv], wm[3][qv]));
+    float mm = wm[0][qv];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, wm[w][qv]);
     f32x4 o = {0.f, 0.f, 0.f, 0.f};
     float ll = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float f = (wm[w][qv] == -INFINITY) ? 0.f : __expf(wm[w][qv] - mm);
-      o += f * *(const f32x4*)&wacc[w][qv][d];
+      o += f * *(const f32x4*)(wacc + ((size_t)w * QV + qv) * HD + d);
       ll += f * wl[w][qv];
     }
-    *(f32x4*)(my_o + qv * HD + d) = o;
-    if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
+    if (FINAL) {
+      // row and head of query vector qv; every row sees at least its own key, so ll > 0
+      const size_t at = (size_t)(b * r_total + rg * rpb + qv / GQ) * ldo + (size_t)(g * GQ + qv % GQ) * HD + d;
+      const float inv_l = 1.0f / ll;
+      bf16_t hi[4], lo[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) split_bf16(o[c] * inv_l, hi[c], lo[c]);
+      *(uint2*)(out + at) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+      *(uint2*)(out_lo + at) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+    } else {
+      *(f32x4*)(my_o + qv * HD + d) = o;
+      if (d == 0) { my_ml[qv * 2] = mm; my_ml[qv * 2 + 1] = ll; }
+    }
   }
 }
 

@@ -433,30 +433,52 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn
 }
 
 // The matrix-core kernel (bf16 caches): one pass over K and V serves up to 16 query vectors per KV head.
+// Two launch shapes.  (1) ONE key range per (row group, KV head, sequence), 8 waves per block, the output written
+// by the kernel itself (no partials, no merge launch): for batches whose (KV head, sequence) pairs fill the chip
+// without splitting.  (2) Key ranges over 4-wave blocks plus the merge: everything else (a single block per KV head
+// would be bound by its matrix-core work: about 1300 cycles per 16 keys and wave).
 template <typename OT, int HD>
-void launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append) {
+hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append) {
   const dmtd_config& cf = c->cfg;
   const int B = c->batch, nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * HD, qd = cf.n_q_heads * HD;
   const int gq = cf.n_q_heads / cf.n_kv_heads, rpb = 16 / gq, n_rg = (r + rpb - 1) / rpb;
-  constexpr int KPI = 64;
+  const int qv_max = (r < rpb ? r : rpb) * gq;             // query vectors of the fullest block
   bf16_t* kc = (bf16_t*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
   bf16_t* vc = (bf16_t*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
   const LayerW& w = c->layers[l];
   const int bucket = c->att_bucket;
   long per_split_blocks = (long)cf.n_kv_heads * B * n_rg;
+  float* po = (float*)(c->ws + c->o.part_o);
+  float* pml = (float*)(c->ws + c->o.part_ml);
+  const DevState* st = dev_state(c);
+  if (per_split_blocks >= c->num_cus) {
+    constexpr int NW = 8;
+    const int kps = (bucket + 16 * NW - 1) / (16 * NW) * (16 * NW);
+    const size_t lds = (size_t)NW * qv_max * HD * 4;
+    auto kern = attn_split_mfma_kernel<HD, NW, true>;
+    static bool big_lds = false;
+    if (lds > 32 * 1024 && !big_lds) {
+      hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, NW * 16 * HD * 4);
+      if (ae != hipSuccess) return ae;
+      big_lds = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(n_rg, cf.n_kv_heads, B), dim3(64 * NW), lds, c->stream, qkv, nqkv,
+                       w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
+                       cf.max_seq_len, cf.rms_eps, kps, 1, kMaxRows * gq, st, sel, offset, r, append, (bf16_t*)attn, (bf16_t*)attn_lo, qd);
+    return hipGetLastError();
+  }
+  constexpr int KPI = 64;
   int want_splits = (int)((4L * c->num_cus + per_split_blocks - 1) / per_split_blocks);
   if (want_splits > ATT_MAX_SPLITS) want_splits = ATT_MAX_SPLITS;
   if (want_splits < 1) want_splits = 1;
   int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
   const int ns = (bucket + kps - 1) / kps;
-  float* po = (float*)(c->ws + c->o.part_o);
-  float* pml = (float*)(c->ws + c->o.part_ml);
-  const DevState* st = dev_state(c);
-  hipLaunchKernelGGL((attn_split_mfma_kernel<HD>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
+  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, 4, false>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), (size_t)4 * qv_max * HD * 4, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
-                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
+                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append, (bf16_t*)nullptr, (bf16_t*)nullptr, 0);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
+  return hipGetLastError();
 }
 
 // Kernel choice.  bf16 caches: the matrix-core kernel (measured faster than the vector kernel even for
@@ -469,9 +491,8 @@ hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* 
   const int gq = cf.n_q_heads / cf.n_kv_heads;
   if (r > kMaxRows) return hipErrorInvalidValue;
   if constexpr (std::is_same<CT, bf16_t>::value) {
-    if (cf.head_dim == 128) launch_attention_mfma_t<OT, 128>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
-    else launch_attention_mfma_t<OT, 64>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
-    return hipGetLastError();
+    if (cf.head_dim == 128) return launch_attention_mfma_t<OT, 128>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
+    return launch_attention_mfma_t<OT, 64>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
   }
   const int want = c->share_kv ? r * gq : gq;
   const int qvt = want <= 4 ? 4 : (want <= 8 ? 8 : 16);
