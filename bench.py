@@ -18,6 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def algorithmic_bytes(sh, n_late, ctx_full, ctx_late_list, batch, n_early=0):
@@ -124,20 +125,31 @@ def main():
     e2e_gbs = total_bytes / dt / 1e9
 
     # roofline of the dominant kernel: RMSNorm + gate/up + SwiGLU weight stream (49 % of a layer's bytes),
-    # launched once per layer back to back, HIP-event timed on the engine's stream
-    rows = min(tau, 4)
+    # launched once per layer back to back, HIP-event timed on the engine's stream, with the activation rows of
+    # this workload's full step (batch x rows per sequence) and of its late-only step (batch)
+    rows = min(B * min(tau, 4), B * 16)
+    rows_late = B
     reps = 10
     per = {}
-    for kind, r in (("gateup", rows), ("gateup", 1), ("down", rows), ("qkv", rows), ("oproj", rows), ("lmhead", 1), ("attn", 1)):
+    for kind, r in (("gateup", rows), ("gateup", rows_late), ("down", rows), ("qkv", rows), ("oproj", rows), ("lmhead", B),
+                    ("attn", 1), ("attn", min(tau, 4))):
         per[f"{kind}_m{r}"] = eng.time_kernel(kind, r, reps)
     gu_bytes = 2 * sh.intermediate * sh.hidden * sh.elem_bytes + sh.hidden * sh.elem_bytes
     achieved = gu_bytes / (per[f"gateup_m{rows}"] * 1e-6) / 1e9
     traffic = measured_traffic(args.workload)
-    roofline = {"bound": "hbm", "kernel": f"gemv_mfma_kernel<SWIGLU, NORM> with {rows} rows (RMSNorm + gate/up + SwiGLU)",
+    kernel_name = "gemv_mfma_kernel<SWIGLU, NORM>" if rows <= 5 else "gemm_mfma_kernel<SWIGLU, NORM> (+ gemm_finish_kernel)"
+    roofline = {"bound": "hbm", "kernel": f"{kernel_name} with {rows} rows (RMSNorm + gate/up + SwiGLU)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": gu_bytes, "avg_launch_us": round(per[f"gateup_m{rows}"], 2),
                 "other_kernels_us": {k: round(v, 2) for k, v in per.items()}}
+    if rows > 16:
+        # batched steps run on the matrix cores in earnest: flops of the same launch (two bf16 activation planes, so
+        # 2 x 2 x rows x N x K multiply-adds) against the dense bf16 peak; the launch stays bound by the weight stream
+        flops = 2.0 * 2.0 * rows * (2 * sh.intermediate) * sh.hidden
+        tf = flops / (per[f"gateup_m{rows}"] * 1e-6) / 1e12
+        roofline["mfma"] = {"flops_per_launch": flops, "achieved_TFLOPs": round(tf, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -325,17 +325,19 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(
   const size_t slot0 = ((size_t)b * nkv + g) * ATT_MAX_SPLITS;
   const size_t qv = (size_t)i * GQ + j;
   float mv = -INFINITY, lv = 0.f;
-  if (tid < n_splits) {
-    const float* p = part_ml + ((slot0 + tid) * qv_stride + qv) * 2;
-    mv = p[0]; lv = p[1];
+  {
+    const float2 ml = *(const float2*)(part_ml + ((slot0 + (tid < n_splits ? tid : 0)) * qv_stride + qv) * 2);
+    if (tid < n_splits) { mv = ml.x; lv = ml.y; }
   }
   const float* po = part_o + ((slot0 + sg) * qv_stride + qv) * HD + d;
   const size_t po_step = (size_t)NG * qv_stride * HD;
   f32x4 ov[PRE];
 #pragma unroll
   for (int u = 0; u < PRE; ++u) {
-    ov[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (sg + u * NG < n_splits) ov[u] = *(const f32x4*)(po + u * po_step);
+    // unconditional, from a clamped range index (a range beyond n_splits gets factor 0 below): a load under a
+    // per-lane condition would be waited for on the spot, one memory round trip after the other
+    const int uc = sg + u * NG < n_splits ? u : 0;
+    ov[u] = *(const f32x4*)(po + uc * po_step);
   }
   const int pos_row = row_base(st, sel, offset, b) + i;    // row i sees keys 0 .. pos_row
   const int n_act = min(n_splits, pos_row / kps + 1);   // ranges that hold keys visible to row i; later ones hold stale partials

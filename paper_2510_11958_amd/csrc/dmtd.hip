@@ -35,29 +35,31 @@ constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile
 constexpr int kGemmRows = 64;        // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 // Waves that split K for one matrix (NW) and k-steps a wave keeps in flight as a rolling window (PF), per projection;
-// NW = 0: the one-round rule of launch_mfma with kMfmaPF.  Defaults from sweeps at 4B shapes on MI355X (us per launch,
-// 3 rows, against the one-round rule): gate/up 20.0 (20.5), down 12.7 (14.3), O 8.2 (8.4), LM head 111.7 (136.7);
-// rolling windows did not help the QKV projection.  O shares down's instantiation (PF 5: its 4 k-steps per wave at 4B
-// shapes plus one empty slot; the PF 4 instantiation spilled registers).  The macros exist so a sweep can override them at build time.
+// NW = 0: the one-round rule of launch_mfma with kMfmaPF.  Defaults from sweeps at 4B shapes on MI355X, us per launch
+// with 3 rows / 1 row: gate/up 4 x 2: 18.9 / 18.1 (4 x 4: 19.5 / 19.1), down 16 x 3: 11.3 / 10.7 (16 x 5: 11.3 / 10.9),
+// O 8 x 4: 6.3 / 6.2 (16 x 5: 8.0 / 7.3), QKV 8 x 2: 7.6 / 7.5 (one round of 5: 8.0 / 7.7); the LM head measures
+// 131 us whatever the shape (it runs at the memory system's rate).  Short windows win since every load of the
+// prologue is issued without a wait in between: the first k-step's matrix-core work starts as soon as it lands.
+// The macros exist so a sweep can override them at build time.
 #ifndef DMTD_GU_NW
 #define DMTD_GU_NW 4
-#define DMTD_GU_PF 4
+#define DMTD_GU_PF 2
 #endif
 #ifndef DMTD_DN_NW
 #define DMTD_DN_NW 16
-#define DMTD_DN_PF 5
+#define DMTD_DN_PF 3
 #endif
 #ifndef DMTD_O_NW
-#define DMTD_O_NW 16
-#define DMTD_O_PF 5
+#define DMTD_O_NW 8
+#define DMTD_O_PF 4
 #endif
 #ifndef DMTD_LM_NW
 #define DMTD_LM_NW 5
 #define DMTD_LM_PF 4
 #endif
 #ifndef DMTD_Q_NW
-#define DMTD_Q_NW 0
-#define DMTD_Q_PF 5
+#define DMTD_Q_NW 8
+#define DMTD_Q_PF 2
 #endif
 constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter runs put 8 waves on a tile (measured 8.3 us instead of 9.3 us at 4B shapes)
 

@@ -108,7 +108,10 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
   float* ss_items = (float*)(xs + (size_t)2 * M_ * K_);   // NORM: the producer's partial sums [n_parts][M], behind the rows
   __shared__ float rs_s[16];
   __shared__ unsigned long long key_s[16];
-  const int tid = threadIdx.x, lane = tid & 63, wall = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wave's index as a scalar: everything derived from it (matrix, k-range, the loads' bounds) then branches
+  // uniformly; left in a vector register, every bounded load became a divergent region the compiler waits on
+  const int wall = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mat = wall / nw, w = wall % nw;
   const int r = lane & 15, kg = lane >> 4;     // B and D: column r
   const int K = K_, N = N_, M = M_;
@@ -122,11 +125,13 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
   f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = acc;
   constexpr bool TWO_ACC = EPI == EPI_RESID && !ROLL;      // where registers allow (one block per CU)
 
-  // small loads first (they return first): the B rows for LDS and the partial sums of squares
+  // small loads first (they return first): the B rows for LDS and the partial sums of squares.  Every one of them is
+  // issued unconditionally, from a clamped index: a load under a per-lane condition makes the compiler wait for it
+  // right there, and each such wait is a full memory round trip in front of the weight stream.
   constexpr int NT = 64 * NWT;
   // registers for the early activation loads: residual projections run one block per CU (few, wide tiles) and can
   // afford to cover long rows; the others stay within 128 registers (two 8-wave blocks per CU)
-  constexpr int NBST = EPI == EPI_RESID ? (ROLL ? 8 : 16) : 3;
+  constexpr int NBST = EPI == EPI_RESID ? (ROLL ? 8 : 16) : 5;
   u32x4 bst[NBST];
   // the rows follow each other in memory (ldxb == K); LDS holds them the same way, the low
   // plane behind the high one, so a 16-byte chunk's source and destination are linear in its index
@@ -138,22 +143,34 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
 #pragma unroll
   for (int j = 0; j < NBST; ++j) {
     const int c = tid + j * NT;
-    if (c < 2 * n_chunks) bst[j] = *chunk_src(c);
+    bst[j] = *chunk_src(c < 2 * n_chunks ? c : 2 * n_chunks - 1);
+  }
+  // NORM: the producer's partial sums of squares, M * n_parts floats: thread (part p = tid / 16 + j * NT / 16, row m = tid % 16)
+  constexpr int NSS = 8;
+  float ssr[NSS];
+  const int ss_m = tid & 15, ss_p0 = tid >> 4;
+  if (NORM) {
+    const float* sp = a.ssp + (ss_m < M ? ss_m : M - 1);
+#pragma unroll
+    for (int j = 0; j < NSS; ++j) {
+      const int p = ss_p0 + j * (NT / 16);
+      ssr[j] = sp[(size_t)(p < a.n_parts ? p : a.n_parts - 1) * a.ssp_ld];
+    }
   }
   u32x4 A[PF][2];
   auto load_a = [&](int base) {
 #pragma unroll
     for (int i = 0; i < PF; ++i) {
-      const int s = base + i;
-      if (s < s1) {
-        A[i][0] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024));
-        A[i][1] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024 + 512));
-      } else {
-        A[i][0] = u32x4{0, 0, 0, 0}; A[i][1] = A[i][0];
-      }
+      // a step beyond the wave's range re-reads the tile's last step (finite values; its B operands are zero below):
+      // unconditional loads straight into the operand registers, nothing for the compiler to merge or wait on
+      const int s = base + i < s1 ? base + i : KS - 1;
+      A[i][0] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024));
+      A[i][1] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)s * 1024 + 512));
     }
   };
+  __builtin_amdgcn_sched_barrier(0);                      // the small loads stay ahead of the weight stream in issue order
   load_a(s0);                                             // the weight stream starts before anything waits
+  __builtin_amdgcn_sched_barrier(0);
   // residual epilogue: this thread's residual value and next-norm gain, fetched now so the epilogue does not wait
   constexpr int EPN = (256 + NT - 1) / NT;
   float hpre[EPN], gpre[EPN];
@@ -167,10 +184,13 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
     }
   }
   if (NORM) {
-    // the producer's partial sums of squares, M * n_parts floats, fetched by all threads while the weights fly
-    for (int p = tid >> 4; p < a.n_parts; p += NT / 16) {
-      const int m = tid & 15;
-      if (m < M) ss_items[p * M + m] = a.ssp[(size_t)p * a.ssp_ld + m];
+    if (ss_m < M) {
+#pragma unroll
+      for (int j = 0; j < NSS; ++j) {
+        const int p = ss_p0 + j * (NT / 16);
+        if (p < a.n_parts) ss_items[p * M + ss_m] = ssr[j];
+      }
+      for (int p = ss_p0 + NSS * (NT / 16); p < a.n_parts; p += NT / 16) ss_items[p * M + ss_m] = a.ssp[(size_t)p * a.ssp_ld + ss_m];
     }
   }
 #pragma unroll
@@ -222,11 +242,9 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][0]), __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[i][1]), __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
         const int sn = s + PF;
-        if (sn < s1) {
+        if (sn < s1) {      // else the slot keeps its (finite) contents: a step beyond the range meets zero B operands
           A[i][0] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)sn * 1024));
           A[i][1] = __builtin_nontemporal_load((const u32x4*)(abase + (size_t)sn * 1024 + 512));
-        } else {
-          A[i][0] = u32x4{0, 0, 0, 0}; A[i][1] = A[i][0];
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -349,12 +367,54 @@ __global__ void __launch_bounds__(256) embed_pack_kernel(
     const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset,
     int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
     float* __restrict__ ssp) {
+  // One pass, 8 elements (16 bytes of the table row) per thread and turn, up to NCH turns' loads in flight at once;
+  // the row's values stay in registers between the fp32 store, the packed store and the sum of squares.
+  constexpr int NCH = 4;
+  __shared__ float wsum[4];
   const int row = blockIdx.x, b = row / r, i = row % r;
   const int pos = row_base(st, sel, offset, b) + i;
   const bf16_t* src = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* dst = h + (size_t)row * d;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = bf16_to_f32(src[k]);
-  pack_row_for_norm(dst, gain, d, xb + (size_t)row * d, xb_lo + (size_t)row * d, ssp + row);
+  bf16_t* ob = xb + (size_t)row * d;
+  bf16_t* ob_lo = xb_lo + (size_t)row * d;
+  const int n_ch = d >> 3;                       // d is a multiple of 64 on this path
+  float ss = 0.f;
+  for (int c0 = threadIdx.x; c0 < n_ch; c0 += NCH * 256) {
+    u32x4 tv[NCH], gv[NCH];
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int c = c0 + u * 256 < n_ch ? c0 + u * 256 : c0;     // unconditional loads from a clamped chunk
+      tv[u] = *(const u32x4*)(src + (size_t)c * 8);
+      gv[u] = *(const u32x4*)(gain + (size_t)c * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int c = c0 + u * 256;
+      if (c < n_ch) {
+        float v[8], g[8];
+        Elem<bf16_t>::unpack(tv[u], v);
+        Elem<bf16_t>::unpack(gv[u], g);
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          bf16_t h0, l0, h1, l1;
+          split_bf16(v[2 * e] * g[2 * e], h0, l0);
+          split_bf16(v[2 * e + 1] * g[2 * e + 1], h1, l1);
+          hi[e] = h0 | ((uint32_t)h1 << 16);
+          lo[e] = l0 | ((uint32_t)l1 << 16);
+          ss += v[2 * e] * v[2 * e] + v[2 * e + 1] * v[2 * e + 1];
+        }
+        *(f32x4*)(dst + (size_t)c * 8) = f32x4{v[0], v[1], v[2], v[3]};
+        *(f32x4*)(dst + (size_t)c * 8 + 4) = f32x4{v[4], v[5], v[6], v[7]};
+        *(u32x4*)(ob + (size_t)c * 8) = u32x4{hi[0], hi[1], hi[2], hi[3]};
+        *(u32x4*)(ob_lo + (size_t)c * 8) = u32x4{lo[0], lo[1], lo[2], lo[3]};
+      }
+    }
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssp[row] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
 }
 
 __global__ void __launch_bounds__(256) take_last_pack_kernel(
