@@ -231,6 +231,24 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
   const int m = blockIdx.y, tid = threadIdx.x;
   const int n0 = (blockIdx.x * 256 + tid) * 4;
   const int N = a.N, M = a.M;
+  const bool act = n0 < N;      // N is a multiple of 16 on this path
+  const int nc = act ? n0 : 0;  // inactive threads load (and drop) the row's first outputs: no load sits under a per-lane condition
+  // Every load of the kernel is issued here, before the first wait: the splits' partial sums (a split beyond ksplit
+  // re-reads the last one and is left out of the sum), the residual row and the next norm's gain.
+  constexpr int KSMAX = EPI == EPI_SWIGLU ? 2 : 8;     // splits fetched up front (gate/up has tiles enough for 2 splits at most at the usual shapes)
+  float4 x[KSMAX], y[KSMAX];
+#pragma unroll
+  for (int ks = 0; ks < KSMAX; ++ks) {
+    const float* p = a.part + ((size_t)(ks < a.ksplit ? ks : a.ksplit - 1) * M + m) * a.ldp + nc;
+    x[ks] = *(const float4*)p;
+    if (EPI == EPI_SWIGLU) y[ks] = *(const float4*)(p + N);
+  }
+  float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  uint2 graw = make_uint2(0u, 0u);
+  if (EPI == EPI_RESID) {
+    h4 = *(const float4*)(a.y + (size_t)m * a.ldy + nc);
+    graw = *(const uint2*)(a.g_next + nc);
+  }
   float rs = 1.f;
   if (NORM) {
     float s = 0.f;
@@ -242,17 +260,21 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
     __syncthreads();
     rs = rs_sh;
   }
-  const bool act = n0 < N;      // N is a multiple of 16 on this path
   float v[4] = {0.f, 0.f, 0.f, 0.f}, v2[4] = {0.f, 0.f, 0.f, 0.f};
-  if (act) {
-    for (int ks = 0; ks < a.ksplit; ++ks) {
-      const float* p = a.part + ((size_t)ks * M + m) * a.ldp + n0;
-      const float4 x = *(const float4*)p;
-      v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
-      if (EPI == EPI_SWIGLU) {
-        const float4 y = *(const float4*)(p + N);
-        v2[0] += y.x; v2[1] += y.y; v2[2] += y.z; v2[3] += y.w;
-      }
+#pragma unroll
+  for (int ks = 0; ks < KSMAX; ++ks) {
+    if (ks < a.ksplit) {
+      v[0] += x[ks].x; v[1] += x[ks].y; v[2] += x[ks].z; v[3] += x[ks].w;
+      if (EPI == EPI_SWIGLU) { v2[0] += y[ks].x; v2[1] += y[ks].y; v2[2] += y[ks].z; v2[3] += y[ks].w; }
+    }
+  }
+  for (int ks = KSMAX; ks < a.ksplit; ++ks) {      // more splits than fetched up front (unusual shapes): one at a time
+    const float* p = a.part + ((size_t)ks * M + m) * a.ldp + nc;
+    const float4 xv = *(const float4*)p;
+    v[0] += xv.x; v[1] += xv.y; v[2] += xv.z; v[3] += xv.w;
+    if (EPI == EPI_SWIGLU) {
+      const float4 yv = *(const float4*)(p + N);
+      v2[0] += yv.x; v2[1] += yv.y; v2[2] += yv.z; v2[3] += yv.w;
     }
   }
   float hsq = 0.f;
@@ -265,12 +287,13 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) { const float gt = v[jj] * rs; o[jj] = gt / (1.0f + __expf(-gt)) * (v2[jj] * rs); }
       } else {
-        float4 h4 = *(const float4*)(a.y + (size_t)m * a.ldy + n0);
         h4.x += v[0]; h4.y += v[1]; h4.z += v[2]; h4.w += v[3];
         *(float4*)(a.y + (size_t)m * a.ldy + n0) = h4;
         const float hn[4] = {h4.x, h4.y, h4.z, h4.w};
+        const float gn[4] = {__uint_as_float(graw.x << 16), __uint_as_float(graw.x & 0xFFFF0000u),
+                             __uint_as_float(graw.y << 16), __uint_as_float(graw.y & 0xFFFF0000u)};
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) { hsq += hn[jj] * hn[jj]; o[jj] = hn[jj] * bf16_to_f32(a.g_next[n0 + jj]); }
+        for (int jj = 0; jj < 4; ++jj) { hsq += hn[jj] * hn[jj]; o[jj] = hn[jj] * gn[jj]; }
       }
       bf16_t hi[4], lo[4];
 #pragma unroll
