@@ -32,6 +32,13 @@ constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
 constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
+#ifndef DMTD_GEMM_STREAMS
+#define DMTD_GEMM_STREAMS 2048
+#endif
+#ifndef DMTD_GEMM_MAXSPLIT
+#define DMTD_GEMM_MAXSPLIT 8
+#endif
+constexpr int kGemmMaxSplit = DMTD_GEMM_MAXSPLIT;   // K splits of the tiled kernel at most (sizes the partial-sum buffer)
 constexpr int kGemmRows = 64;        // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 // Waves that split K for one matrix (NW) and k-steps a wave keeps in flight as a rolling window (PF), per projection;
@@ -199,7 +206,7 @@ Ws layout(const dmtd_config& c) {
     {
       size_t widest = 2 * (size_t)c.intermediate > nqkv ? 2 * (size_t)c.intermediate : nqkv;
       if (d > widest) widest = d;
-      w.gemm_part = take((size_t)8 * kGemmRows * widest * 4);
+      w.gemm_part = take((size_t)kGemmMaxSplit * kGemmRows * widest * 4);
     }
     w.wsw = take((swizzled_layer_elems(c) * c.n_layers + swizzled_elems(c.vocab, d)) * 2);
   }
@@ -322,9 +329,9 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       const int KS = a.K / 64;
       int ksplit = 1;
       if constexpr (EPI != EPI_LOGITS) {
-        ksplit = (2048 + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
-        if (ksplit > 8) ksplit = 8;
-        if (ksplit > KS / 3) ksplit = KS / 3 > 0 ? KS / 3 : 1;
+        ksplit = (DMTD_GEMM_STREAMS + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
+        if (ksplit > kGemmMaxSplit) ksplit = kGemmMaxSplit;
+        if (ksplit > KS / DMTD_GEMM_PF) ksplit = KS / DMTD_GEMM_PF > 0 ? KS / DMTD_GEMM_PF : 1;
       }
       if (ksplit > 1) {
         if constexpr (EPI != EPI_LOGITS) {

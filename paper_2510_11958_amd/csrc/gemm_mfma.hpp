@@ -19,9 +19,25 @@
 // and gemm_finish_kernel adds them in order and runs the epilogue.  The LM head (thousands of tiles)
 // runs unsplit with the epilogue in this kernel.
 #pragma once
+#include <type_traits>
 #include "gemv_mfma.hpp"
 
 namespace dmtd {
+
+#ifndef DMTD_GEMM_PF
+#define DMTD_GEMM_PF 3
+#endif
+#ifndef DMTD_GEMM_KSMAX_GU
+#define DMTD_GEMM_KSMAX_GU 2
+#endif
+// compile-time loop: f(integral_constant<int, I>) for I in [I0, N)
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>());
+    static_for<I + 1, N>(f);
+  }
+}
 
 constexpr int GEMM_WAVES = 4;
 constexpr int GEMM_TILES_PER_BLOCK = 8;     // weight tiles of 16 outputs a block owns (SwiGLU: 4 gate + 4 up)
@@ -29,7 +45,9 @@ constexpr int GEMM_TILES_PER_BLOCK = 8;     // weight tiles of 16 outputs a bloc
 template <int EPI, bool NORM, int CG, bool SPLITK>
 __global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) {
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
-  constexpr int PF = 3;                  // k-steps in flight
+  // k-steps in flight: 3; 2 with 64 rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
+  // gate/up 37.4 against 38.8 us, QKV 19.9 against 21.9)
+  constexpr int PF = CG == 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF;
   constexpr int LDB = 72;                // LDS row: 64 values + 8 of padding
   constexpr int NT = 64 * GEMM_WAVES;
   constexpr int PIECES = 2 * BM * 8;     // 16-byte pieces of one k-step's activation slice (2 planes)
@@ -74,19 +92,19 @@ __global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) 
 
   u32x4 A[PF][2][2];     // [slot][tile][half of the k-step]
   u32x4 Bq[PF][PPT];
-  auto issue = [&](int s, int slot) {      // slot is a compile-time constant at every call
-    if (s < s_hi) {
+  auto issue_always = [&](int s, int slot) {      // slot is a compile-time constant at every call
 #pragma unroll
-      for (int i = 0; i < PPT; ++i) Bq[slot][i] = *(const u32x4*)(bsrc[i] + (size_t)s * 64);
+    for (int i = 0; i < PPT; ++i) Bq[slot][i] = *(const u32x4*)(bsrc[i] + (size_t)s * 64);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        A[slot][j][0] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024));
-        A[slot][j][1] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024 + 512));
-      }
+    for (int j = 0; j < 2; ++j) {
+      A[slot][j][0] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024));
+      A[slot][j][1] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024 + 512));
     }
   };
+  // the first PF steps, unconditionally (a range shorter than PF re-reads its last step into slots no step consumes):
+  // a bounds check here would leave the compiler unsure which loads are in flight at the head of the main loop
 #pragma unroll
-  for (int s = 0; s < PF; ++s) issue(s_lo + s, s);
+  for (int s = 0; s < PF; ++s) issue_always(s_lo + s < s_hi ? s_lo + s : s_hi - 1, s);
 
   f32x4 acc[2][CG];
 #pragma unroll
@@ -94,7 +112,8 @@ __global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) 
 #pragma unroll
     for (int g = 0; g < CG; ++g) acc[j][g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto step = [&](int s, int slot) {
+  auto step = [&](int s, int slot, auto mode_c) {
+    constexpr int MODE = decltype(mode_c)::value;
     bf16_t* buf = &bs[s & 1][0][0][0];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) *(u32x4*)(buf + bdst[i]) = Bq[slot][i];
@@ -113,12 +132,38 @@ __global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) 
         }
       }
     }
-    issue(s + PF, slot);
+    // MODE 1: the step PF ahead exists for certain: an unconditional issue, so the compiler knows how many loads are
+    // in flight at every wait and a step waits for its own loads only (behind a bounds check it has to assume the
+    // worst at the loop head and drains every load each round).  MODE 0: nothing left to fetch.
+    if (MODE == 1) issue_always(s + PF, slot);
   };
-  for (int s0 = s_lo; s0 < s_hi; s0 += PF) {
+  int s0 = s_lo;
+  for (; s0 + 2 * PF <= s_hi; s0 += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) step(s0 + u, u, std::integral_constant<int, 1>());
+  }
+  // R < 2 PF steps left.  R >= PF: steps u < R - PF still have a step PF ahead (issued without a check, so the waits stay
+  // exact), the others have none; one straight-line copy per R.  R < PF (a k-range shorter than the pipeline): plain steps.
+  auto tail = [&](auto r_c) {
+    constexpr int R = decltype(r_c)::value;
+    static_for<0, PF>([&](auto u) {
+      constexpr int U = decltype(u)::value;
+      step(s0 + U, U, std::integral_constant<int, (U + PF < R) ? 1 : 0>());
+    });
+    static_for<0, R - PF>([&](auto u) {
+      constexpr int U = decltype(u)::value;
+      step(s0 + PF + U, U, std::integral_constant<int, 0>());
+    });
+  };
+  const int rem = s_hi - s0;
+  if (rem >= PF) {
+    static_for<PF, 2 * PF>([&](auto r) {
+      if (rem == decltype(r)::value) tail(r);
+    });
+  } else {
 #pragma unroll
     for (int u = 0; u < PF; ++u)
-      if (s0 + u < s_hi) step(s0 + u, u);
+      if (s0 + u < s_hi) step(s0 + u, u, std::integral_constant<int, 0>());
   }
 
   if (SPLITK) {
@@ -235,7 +280,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
   const int nc = act ? n0 : 0;  // inactive threads load (and drop) the row's first outputs: no load sits under a per-lane condition
   // Every load of the kernel is issued here, before the first wait: the splits' partial sums (a split beyond ksplit
   // re-reads the last one and is left out of the sum), the residual row and the next norm's gain.
-  constexpr int KSMAX = EPI == EPI_SWIGLU ? 2 : 8;     // splits fetched up front (gate/up has tiles enough for 2 splits at most at the usual shapes)
+  constexpr int KSMAX = EPI == EPI_SWIGLU ? DMTD_GEMM_KSMAX_GU : 8;     // splits fetched up front (gate/up has tiles enough for 2 splits at most at the usual shapes)
   float4 x[KSMAX], y[KSMAX];
 #pragma unroll
   for (int ks = 0; ks < KSMAX; ++ks) {
