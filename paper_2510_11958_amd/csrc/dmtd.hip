@@ -314,7 +314,6 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
   if (!fits) {
     const int n_tiles = (a.N + 15) / 16;
-    const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + GEMM_WAVES - 1) / GEMM_WAVES : (n_tiles + GEMM_TILES_PER_BLOCK - 1) / GEMM_TILES_PER_BLOCK);
     for (int m0 = 0; m0 < rows; m0 += kGemmRows) {
       MfmaArgs g = a;
       g.M = rows - m0 < kGemmRows ? rows - m0 : kGemmRows;
@@ -325,13 +324,16 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
       if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
       if (a.amax) g.amax = a.amax + m0;
+      const int cg = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
+      const int gw = gemm_waves(cg, EPI);                  // a wave owns 2 tiles (SwiGLU: the gate and up tile of one)
+      const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + gw - 1) / gw : (n_tiles + 2 * gw - 1) / (2 * gw));
       // enough k-steps in flight for HBM: about 2048 (tile, split) streams; the LM head has them without splitting
       const int KS = a.K / 64;
       int ksplit = 1;
       if constexpr (EPI != EPI_LOGITS) {
-        ksplit = (DMTD_GEMM_STREAMS + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
-        if (ksplit > kGemmMaxSplit) ksplit = kGemmMaxSplit;
-        if (ksplit > KS / DMTD_GEMM_PF) ksplit = KS / DMTD_GEMM_PF > 0 ? KS / DMTD_GEMM_PF : 1;
+        ksplit = (2048 + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
+        if (ksplit > 8) ksplit = 8;
+        if (ksplit > KS / 3) ksplit = KS / 3 > 0 ? KS / 3 : 1;
       }
       if (ksplit > 1) {
         if constexpr (EPI != EPI_LOGITS) {
@@ -339,15 +341,15 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
           g.ldp = (EPI == EPI_SWIGLU ? 2 : 1) * a.N;
           g.part = (float*)(c->ws + c->o.gemm_part);
           const dim3 sgrid(ggrid.x, ksplit);
-          if (g.M <= 16) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
-          else if (g.M <= 32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
-          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+          if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
+          else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
+          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
           hipLaunchKernelGGL((gemm_finish_kernel<EPI, NORM>), dim3((a.N / 4 + 255) / 256, g.M), dim3(256), 0, c->stream, g);
         }
       } else {
-        if (g.M <= 16) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
-        else if (g.M <= 32) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
-        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * GEMM_WAVES), 0, c->stream, g);
+        if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
+        else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
+        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
       }
     }
     return hipGetLastError();

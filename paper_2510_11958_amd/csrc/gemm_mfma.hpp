@@ -39,11 +39,15 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-constexpr int GEMM_WAVES = 4;
-constexpr int GEMM_TILES_PER_BLOCK = 8;     // weight tiles of 16 outputs a block owns (SwiGLU: 4 gate + 4 up)
+// Waves per block (a wave owns 2 weight tiles; SwiGLU: the gate and up tile of the same outputs).  With 32 and more rows a
+// k-step's slice of activations is as big as the weights a 4-wave block streams against it, so projections with many
+// tiles put 8 waves on a slice (measured at 4B shapes, 64 rows: gate/up 32.8 against 37.4 us, QKV 18.7 against 19.9);
+// the residual projections have few tiles (160) and would leave most of the chip idle (down: 26.5 against 20.6 us).
+constexpr int gemm_waves(int cg, int epi) { return (cg >= 2 && epi != EPI_RESID) ? 8 : 4; }
 
 template <int EPI, bool NORM, int CG, bool SPLITK>
-__global__ void __launch_bounds__(64 * GEMM_WAVES) gemm_mfma_kernel(MfmaArgs a) {
+__global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(MfmaArgs a) {
+  constexpr int GEMM_WAVES = gemm_waves(CG, EPI);
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
   // k-steps in flight: 3; 2 with 64 rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
   // gate/up 37.4 against 38.8 us, QKV 19.9 against 21.9)
