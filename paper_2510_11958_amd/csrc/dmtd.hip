@@ -39,7 +39,10 @@ constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile
 #define DMTD_GEMM_MAXSPLIT 8
 #endif
 constexpr int kGemmMaxSplit = DMTD_GEMM_MAXSPLIT;   // K splits of the tiled kernel at most (sizes the partial-sum buffer)
-constexpr int kGemmRows = 64;        // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
+#ifndef DMTD_GEMM_ROWS
+#define DMTD_GEMM_ROWS 128
+#endif
+constexpr int kGemmRows = DMTD_GEMM_ROWS;   // activation rows per pass of the LDS-tiled MFMA kernel (launches with more than 16 rows)
 constexpr int kMfmaPF = 10;          // k-steps (64 elements) a wave of the MFMA kernel holds in registers
 // Waves that split K for one matrix (NW) and k-steps a wave keeps in flight as a rolling window (PF), per projection;
 // NW = 0: the one-round rule of launch_mfma with kMfmaPF.  Defaults from sweeps at 4B shapes on MI355X, us per launch
@@ -324,7 +327,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       if (a.yb) { g.yb = a.yb + (size_t)m0 * a.ldyb; g.yb_lo = a.yb_lo + (size_t)m0 * a.ldyb; }
       if (a.ssp_next) g.ssp_next = a.ssp_next + m0;
       if (a.amax) g.amax = a.amax + m0;
-      const int cg = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
+      const int cg = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : (g.M <= 64 ? 4 : 8));
       const int gw = gemm_waves(cg, EPI);                  // a wave owns 2 tiles (SwiGLU: the gate and up tile of one)
       const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + gw - 1) / gw : (n_tiles + 2 * gw - 1) / (2 * gw));
       // enough k-steps in flight for HBM: about 2048 (tile, split) streams; the LM head has them without splitting
@@ -343,13 +346,15 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
           const dim3 sgrid(ggrid.x, ksplit);
           if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
           else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
-          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
+          else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
+          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, true>), sgrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g);
           hipLaunchKernelGGL((gemm_finish_kernel<EPI, NORM>), dim3((a.N / 4 + 255) / 256, g.M), dim3(256), 0, c->stream, g);
         }
       } else {
         if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
         else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
-        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
+        else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
+        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, false>), ggrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g);
       }
     }
     return hipGetLastError();

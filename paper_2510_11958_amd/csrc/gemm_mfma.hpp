@@ -43,7 +43,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 // k-step's slice of activations is as big as the weights a 4-wave block streams against it, so projections with many
 // tiles put 8 waves on a slice (measured at 4B shapes, 64 rows: gate/up 32.8 against 37.4 us, QKV 18.7 against 19.9);
 // the residual projections have few tiles (160) and would leave most of the chip idle (down: 26.5 against 20.6 us).
-constexpr int gemm_waves(int cg, int epi) { return (cg >= 2 && epi != EPI_RESID) ? 8 : 4; }
+// With 128 rows the accumulators leave registers for 8 waves only in the SwiGLU kernel (the others would spill).
+constexpr int gemm_waves(int cg, int epi) { return (cg >= 2 && epi != EPI_RESID && (cg <= 4 || epi == EPI_SWIGLU)) ? 8 : 4; }
 
 template <int EPI, bool NORM, int CG, bool SPLITK>
 __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(MfmaArgs a) {
@@ -51,7 +52,7 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
   // k-steps in flight: 3; 2 with 64 rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
   // gate/up 37.4 against 38.8 us, QKV 19.9 against 21.9)
-  constexpr int PF = CG == 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF;
+  constexpr int PF = CG >= 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF;
   constexpr int LDB = 72;                // LDS row: 64 values + 8 of padding
   constexpr int NT = 64 * GEMM_WAVES;
   constexpr int PIECES = 2 * BM * 8;     // 16-byte pieces of one k-step's activation slice (2 planes)
