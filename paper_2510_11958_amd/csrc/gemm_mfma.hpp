@@ -111,6 +111,28 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
 #pragma unroll
   for (int s = 0; s < PF; ++s) issue_always(s_lo + s < s_hi ? s_lo + s : s_hi - 1, s);
 
+  if (NORM && !SPLITK) {
+    // the rows' 1/rms while the first weights are on their way: wave w takes rows w, w + waves, ..., its lanes the producer's
+    // partial sums of squares, four loads per lane in flight (one thread per row walking all parts in turn cost every block
+    // of the LM head ~160 dependent loads in its epilogue: 210 us per launch in the step against 147 with a single part)
+    for (int m = w; m < M; m += GEMM_WAVES) {
+      float sacc = 0.f;
+      for (int p0 = 0; p0 < a.n_parts; p0 += 256) {
+        float v4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int p = p0 + lane + 64 * j;
+          v4[j] = a.ssp[(size_t)(p < a.n_parts ? p : a.n_parts - 1) * a.ssp_ld + m];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (p0 + lane + 64 * j < a.n_parts) sacc += v4[j];
+      }
+      sacc = wave_sum(sacc);
+      if (lane == 0) rs_s[m] = rsqrtf(sacc / (float)K + a.eps);
+    }
+  }
+
   f32x4 acc[2][CG];
 #pragma unroll
   for (int j = 0; j < 2; ++j)
@@ -190,14 +212,7 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
 
   // ---- epilogue: lane (column r of group g = activation row g*16 + r, kg) holds outputs tile*16 + kg*4 + 0..3
   if (tid < BM) key_s[tid] = 0ull;
-  if (NORM) {
-    if (tid < M) {
-      float s = 0.f;
-      for (int p = 0; p < a.n_parts; ++p) s += a.ssp[(size_t)p * a.ssp_ld + tid];
-      rs_s[tid] = rsqrtf(s / (float)K + a.eps);
-    }
-  }
-  __syncthreads();
+  __syncthreads();                       // rs_s (written before the main loop) and key_s are visible
 #pragma unroll
   for (int g = 0; g < CG; ++g) {
     const int m = g * 16 + r;
