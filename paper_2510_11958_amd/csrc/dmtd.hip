@@ -39,6 +39,9 @@ constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile
 #define DMTD_GEMM_MAXSPLIT 8
 #endif
 constexpr int kGemmMaxSplit = DMTD_GEMM_MAXSPLIT;   // K splits of the tiled kernel at most (sizes the partial-sum buffer)
+#ifndef DMTD_FIT_SMALL_KB
+#define DMTD_FIT_SMALL_KB 60
+#endif
 #ifndef DMTD_GEMM_ROWS
 #define DMTD_GEMM_ROWS 128
 #endif
@@ -299,7 +302,7 @@ hipError_t gemv_rows(dmtd_ctx* c, GemvArgs a, int rows) {
 
 // nw waves split K for each matrix: the smallest of {2, 4, 8} (SwiGLU: {2, 4, 5}) that lets a wave
 // hold its k-range in one round of PF k-steps, else the largest with several rounds.
-// More than 16 rows go through the LDS-tiled kernel, 64 per pass (each pass streams the matrix once).
+// More than 16 rows go through the LDS-tiled kernel, up to kGemmRows per pass (each pass streams the matrix once).
 template <int EPI, bool NORM, int PF = kMfmaPF, int ROLL_NW = 0>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
@@ -312,9 +315,9 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const dim3 grid((a.N + 15) / 16);
   // The one-tile-per-block kernel keeps all rows (both planes) in LDS: comfortably (two blocks per CU) in general,
   // up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway.  Rows that do not
-  // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to 64 rows.
+  // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to kGemmRows rows.
   const size_t lds_rows = (size_t)(rows < kMfmaRows ? rows : kMfmaRows) * ((size_t)4 * a.K + (NORM ? (size_t)a.n_parts * 4 : 0));
-  const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)60 * 1024);
+  const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)DMTD_FIT_SMALL_KB * 1024);
   if (!fits) {
     const int n_tiles = (a.N + 15) / 16;
     for (int m0 = 0; m0 < rows; m0 += kGemmRows) {

@@ -1,17 +1,20 @@
-// Weight-streaming projection for 17..64 activation rows of a bf16 model on gfx950 (batched
-// decode steps, refill rows of several sequences, prefill of a batch): the rows form CG groups
-// of 16 MFMA columns and ONE pass over the weights serves them all.
+// Weight-streaming projection for 6..128 activation rows of a bf16 model on gfx950 (batched
+// decode steps, refill rows of several sequences, prefill of a batch): the rows form CG = 1, 2, 4 or 8
+// groups of 16 MFMA columns and ONE pass over the weights serves them all.
 //
 // With this many rows the activations no longer fit in LDS whole, and a block that owned one
 // 16-row weight tile (as the 1..16-row kernel does) would pull every activation through L2 again
-// for every tile.  Here a block of 4 waves owns 8 weight tiles (2 per wave; SwiGLU: the gate and
-// the up tile of the same 16 outputs) and walks K in steps of 64:
-//   * weights: operand-order tiles straight from HBM into registers, 3 k-steps ahead per wave;
+// for every tile.  Here a wave owns 2 weight tiles (SwiGLU: the gate and the up tile of the same 16
+// outputs), a block has 4 or 8 waves (gemm_waves) and walks K in steps of 64:
+//   * weights: operand-order tiles straight from HBM into registers, PF = 3 k-steps ahead per wave
+//     (2 with 64 and more rows);
 //   * activations: the k-step's slice of all rows, both bf16 planes (see gemv_mfma.hpp), fetched
-//     by all threads 3 k-steps ahead into registers, written to one of two LDS buffers and shared
-//     by the block's 8 tiles, every B fragment feeding the matrix cores twice (one per tile of a wave).
+//     by all threads as far ahead into registers, written to one of two LDS buffers and shared
+//     by the block's tiles, every B fragment feeding the matrix cores twice (one per tile of a wave).
 // One block barrier per k-step.  A wave owns its tiles over the block's whole k-range, so nothing is
-// reduced across waves.
+// reduced across waves.  The loop is laid out so that every wait counts exactly the loads that may stay
+// in flight: the first PF steps are issued without a bounds check, the main loop covers only steps whose
+// successor PF ahead exists, and the tail is one straight-line copy per number of remaining steps.
 //
 // Memory-level parallelism: a tile has 3 k-steps (6 KiB) in flight, so a projection with few tiles
 // (QKV 384, O and down 160 at 4B shapes) would keep only 1-2 MB in flight, far below what HBM needs
@@ -50,7 +53,7 @@ template <int EPI, bool NORM, int CG, bool SPLITK>
 __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(MfmaArgs a) {
   constexpr int GEMM_WAVES = gemm_waves(CG, EPI);
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
-  // k-steps in flight: 3; 2 with 64 rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
+  // k-steps in flight: 3; 2 with 64 and more rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
   // gate/up 37.4 against 38.8 us, QKV 19.9 against 21.9)
   constexpr int PF = CG >= 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF;
   constexpr int LDB = 72;                // LDS row: 64 values + 8 of padding
