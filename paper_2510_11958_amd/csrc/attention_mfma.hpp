@@ -49,13 +49,63 @@ template <int HD> struct AttRowLane {
   typedef float fvec_t __attribute__((ext_vector_type(HD / 32)));
   typedef unsigned short hvec_t __attribute__((ext_vector_type(HD / 32)));
 };
+// Where the launch's q/k/v rows come from: the finished fp32 rows [rows][ldq], or - when the QKV projection ran with K
+// split over blocks and left its finishing step to this kernel - the splits' raw partial sums part[split][M][ldp] together
+// with what their norm scale is made of (the producer's partial sums of squares ssp[part][ssp_ld] of the projection's
+// input rows; scale = rsqrt(sum / K + eps)).  The sum over the splits is taken in split order, as the finishing kernel does.
+struct QkvSrc {
+  const float* qkv; int ldq;
+  const float* part; int ksplit, M, ldp;
+  const float* ssp; int n_parts, ssp_ld;
+  float inv_k, eps;
+};
+constexpr int ATT_KSMAX = 8;      // splits fetched at once (the projection splits K at most 8 ways)
+
+// The 2 * HL elements lane l of a 16-lane row holds of the vector at (row_g, element offset col): every load is issued
+// before the first use; called by whole 16-lane rows (the scale's sum of squares is a row reduction).
+template <int HD>
+__device__ __forceinline__ void attn_load_vec(const QkvSrc& q, int row_g, int col, int l,
+                                              typename AttRowLane<HD>::fvec_t& xa, typename AttRowLane<HD>::fvec_t& xb) {
+  typedef typename AttRowLane<HD>::fvec_t fvec_t;
+  constexpr int HL = AttRowLane<HD>::HL, half = HD / 2;
+  if (!q.part) {
+    const float* src = q.qkv + (size_t)row_g * q.ldq + col + HL * l;
+    xa = *(const fvec_t*)src; xb = *(const fvec_t*)(src + half);
+    return;
+  }
+  fvec_t pa[ATT_KSMAX], pb[ATT_KSMAX];
+#pragma unroll
+  for (int ks = 0; ks < ATT_KSMAX; ++ks) {
+    const float* p = q.part + ((size_t)(ks < q.ksplit ? ks : q.ksplit - 1) * q.M + row_g) * q.ldp + col + HL * l;
+    pa[ks] = *(const fvec_t*)p; pb[ks] = *(const fvec_t*)(p + half);
+  }
+  float ss = 0.f;
+  for (int p0 = 0; p0 < q.n_parts; p0 += 64) {
+    float sp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int pi = p0 + l + 16 * j;
+      sp[j] = q.ssp[(size_t)(pi < q.n_parts ? pi : q.n_parts - 1) * q.ssp_ld + row_g];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (p0 + l + 16 * j < q.n_parts) ss += sp[j];
+  }
+  const float rs = rsqrtf(row16_sum(ss) * q.inv_k + q.eps);
+  fvec_t sa = pa[0], sb = pb[0];
+#pragma unroll
+  for (int ks = 1; ks < ATT_KSMAX; ++ks)
+    if (ks < q.ksplit) { sa += pa[ks]; sb += pb[ks]; }
+  xa = sa * rs; xb = sb * rs;
+}
+
 // The block's query vector of row group lane group grp (if any): loaded before the positions are known.
 template <int HD> struct AttQueryPre {
   typename AttRowLane<HD>::fvec_t xa, xb;
   typename AttRowLane<HD>::hvec_t g0, g1;
 };
 template <int HD>
-__device__ __forceinline__ AttQueryPre<HD> attn_preload_query(const float* __restrict__ qkv, int ldq, const bf16_t* __restrict__ q_gain,
+__device__ __forceinline__ AttQueryPre<HD> attn_preload_query(const QkvSrc& qs, const bf16_t* __restrict__ q_gain,
                                                               int b, int g, int GQ, int r_total, int row0, int QV, int tid) {
   typedef typename AttRowLane<HD>::fvec_t fvec_t;
   typedef typename AttRowLane<HD>::hvec_t hvec_t;
@@ -64,9 +114,8 @@ __device__ __forceinline__ AttQueryPre<HD> attn_preload_query(const float* __res
   AttQueryPre<HD> p;
 #pragma unroll
   for (int e = 0; e < HL; ++e) { p.xa[e] = 0.f; p.xb[e] = 0.f; p.g0[e] = 0; p.g1[e] = 0; }
-  if (v < QV) {
-    const float* src = qkv + (size_t)(b * r_total + row0 + v / GQ) * ldq + (size_t)(g * GQ + v % GQ) * HD + HL * l;
-    p.xa = *(const fvec_t*)src; p.xb = *(const fvec_t*)(src + half);
+  if (v < QV) {     // whole 16-lane rows: v is uniform within one
+    attn_load_vec<HD>(qs, b * r_total + row0 + v / GQ, (g * GQ + v % GQ) * HD, l, p.xa, p.xb);
     p.g0 = *(const hvec_t*)(q_gain + HL * l); p.g1 = *(const hvec_t*)(q_gain + half + HL * l);
   }
   return p;
@@ -80,7 +129,7 @@ __device__ __forceinline__ AttQueryPre<HD> attn_preload_query(const float* __res
 // loaded as vectors, so the block's 16 rows take 16 vectors at a time and the sum of squares needs no LDS traffic.
 template <int HD>
 __device__ __forceinline__ void attn_prepare_rows_mfma(
-    const float* __restrict__ qkv, int ldq, const bf16_t* __restrict__ q_gain, const bf16_t* __restrict__ k_gain,
+    const QkvSrc& qs, const bf16_t* __restrict__ q_gain, const bf16_t* __restrict__ k_gain,
     const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int b, int g, int nh, int nkv, int s_max,
     float eps, int r_total, int row0, int QV, int n_new, bool holds_new, bool writer, int pos_first, int key_begin, int key_end,
     bf16_t (*qhi_s)[HD + ATT_QPAD], bf16_t (*qlo_s)[HD + ATT_QPAD], float (*knew_s)[HD], float (*vnew_s)[HD], int tid,
@@ -97,9 +146,8 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
     const bool is_q = v < QV, is_k = !is_q && v < QV + n_new;
     const int row = is_q ? row0 + v / GQ : (is_k ? v - QV : v - QV - n_new);       // row of the launch
     const int hcol = is_q ? g * GQ + v % GQ : (is_k ? nh + g : nh + nkv + g);
-    const float* src = qkv + (size_t)(b * r_total + row) * ldq + (size_t)hcol * HD + HL * l;
     fvec_t xa = pre.xa, xb = pre.xb;          // queries (all in the first round: QV <= 16 <= n_groups) were fetched at kernel entry
-    if (!is_q) { xa = *(const fvec_t*)src; xb = *(const fvec_t*)(src + half); }
+    if (!is_q) attn_load_vec<HD>(qs, b * r_total + row, hcol * HD, l, xa, xb);
     float x0[HL], x1[HL];
 #pragma unroll
     for (int e = 0; e < HL; ++e) { x0[e] = xa[e]; x1[e] = xb[e]; }
@@ -167,7 +215,7 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
 // results meet in dynamic shared memory: NW * QV * HD floats (QV = the block's query vectors).
 template <int HD, int NW, bool FINAL>
 __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
-    const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
+    QkvSrc qs, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
     const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
     float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
     int kps /* keys per range, a multiple of 16 * NW */, int n_splits, int qv_stride,
@@ -219,7 +267,7 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
   load_kv(key_begin + 16 * wave, range_limit);
 
   // the block's query vectors do not depend on the positions: fetched now, next to K and V
-  const AttQueryPre<HD> qpre = attn_preload_query<HD>(qkv, ldq, (const bf16_t*)q_gain, b, g, GQ, r_total, rg * rpb, QV, tid);
+  const AttQueryPre<HD> qpre = attn_preload_query<HD>(qs, (const bf16_t*)q_gain, b, g, GQ, r_total, rg * rpb, QV, tid);
 
   const int pos_first = row_base(st, sel, offset, b);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
@@ -230,7 +278,7 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
   const bool holds_new = key_end > pos_first;
   const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
 
-  attn_prepare_rows_mfma<HD>(qkv, ldq, (const bf16_t*)q_gain, (const bf16_t*)k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total,
+  attn_prepare_rows_mfma<HD>(qs, (const bf16_t*)q_gain, (const bf16_t*)k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total,
                              rg * rpb, QV, n_new, holds_new, writer, pos_first, key_begin, key_end, qhi_s, qlo_s, knew_s, vnew_s, tid, NT / 16, qpre);
   __syncthreads();
 
