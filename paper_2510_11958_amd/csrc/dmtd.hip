@@ -32,11 +32,8 @@ constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
 constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
-#ifndef DMTD_GEMM_STREAMS
-#define DMTD_GEMM_STREAMS 2048
-#endif
 #ifndef DMTD_GEMM_MAXSPLIT
-#define DMTD_GEMM_MAXSPLIT 8
+#define DMTD_GEMM_MAXSPLIT 12
 #endif
 constexpr int kGemmMaxSplit = DMTD_GEMM_MAXSPLIT;   // K splits of the tiled kernel at most (sizes the partial-sum buffer)
 #ifndef DMTD_FIT_SMALL_KB
@@ -343,12 +340,18 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       const int cg = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : (g.M <= 64 ? 4 : 8));
       const int gw = gemm_waves(cg, EPI);                  // a wave owns 2 tiles (SwiGLU: the gate and up tile of one)
       const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + gw - 1) / gw : (n_tiles + 2 * gw - 1) / (2 * gw));
-      // enough k-steps in flight for HBM: about 2048 (tile, split) streams; the LM head has them without splitting
+      // K is split so that the launch has about one block per CU and no more (a second round of blocks costs more than
+      // it brings; measured at 4B shapes, 128 rows: QKV 288 blocks 32.4 us, 240 blocks 24.4 us; gate/up 152 blocks 50.0 us,
+      // 228 blocks 42.4 us, 304 blocks 57.3 us; down 160 / 240 / 320 blocks 31.6 / 27.0 / 38.1 us); the LM head has
+      // blocks enough without splitting
       const int KS = a.K / 64;
       int ksplit = 1;
       if constexpr (EPI != EPI_LOGITS) {
-        ksplit = (2048 + n_tiles * (EPI == EPI_SWIGLU ? 2 : 1) - 1) / (n_tiles * (EPI == EPI_SWIGLU ? 2 : 1));
-        if (ksplit > 8) ksplit = 8;
+        ksplit = c->num_cus / (int)ggrid.x;
+        if (ksplit < 1) ksplit = 1;
+        if (EPI == EPI_STORE && ksplit > ATT_KSMAX) ksplit = ATT_KSMAX;      // what the attention launch can sum in its prologue
+        if (EPI == EPI_RESID && ksplit > KS / 8) ksplit = KS / 8 > 0 ? KS / 8 : 1;
+        if (ksplit > kGemmMaxSplit) ksplit = kGemmMaxSplit;
         if (ksplit > KS / 3) ksplit = KS / 3 > 0 ? KS / 3 : 1;
         // gate/up with up to 16 rows: its 1216 tile streams do without a split, and without the finishing launch (4B shapes,
         // 8 rows: 20.3 against 24.2 us); with 32 and more rows the 8-wave blocks are too few unsplit (36 against 24 us)

@@ -30,8 +30,11 @@ namespace dmtd {
 #ifndef DMTD_GEMM_PF
 #define DMTD_GEMM_PF 3
 #endif
+#ifndef DMTD_GEMM_KSMAX
+#define DMTD_GEMM_KSMAX 12
+#endif
 #ifndef DMTD_GEMM_KSMAX_GU
-#define DMTD_GEMM_KSMAX_GU 2
+#define DMTD_GEMM_KSMAX_GU 3
 #endif
 // compile-time loop: f(integral_constant<int, I>) for I in [I0, N)
 template <int I, int N, typename F>
@@ -303,7 +306,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
   const int nc = act ? n0 : 0;  // inactive threads load (and drop) the row's first outputs: no load sits under a per-lane condition
   // Every load of the kernel is issued here, before the first wait: the splits' partial sums (a split beyond ksplit
   // re-reads the last one and is left out of the sum), the residual row and the next norm's gain.
-  constexpr int KSMAX = EPI == EPI_SWIGLU ? DMTD_GEMM_KSMAX_GU : 8;     // splits fetched up front (gate/up has tiles enough for 2 splits at most at the usual shapes)
+  constexpr int KSMAX = EPI == EPI_SWIGLU ? DMTD_GEMM_KSMAX_GU : DMTD_GEMM_KSMAX;     // splits fetched up front (gate/up has blocks enough with 3 splits at most at the usual shapes)
   float4 x[KSMAX], y[KSMAX];
 #pragma unroll
   for (int ks = 0; ks < KSMAX; ++ks) {
