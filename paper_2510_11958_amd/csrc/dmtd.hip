@@ -363,10 +363,10 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
           g.ldp = (EPI == EPI_SWIGLU ? 2 : 1) * a.N;
           g.part = (float*)(c->ws + c->o.gemm_part);
           const dim3 sgrid(ggrid.x, ksplit);
-          if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
-          else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
-          else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
-          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, true>), sgrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g);
+          if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+          else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+          else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, true>), sgrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
           if (EPI == EPI_STORE && NORM && c->fold_qkv && rows <= kGemmRows && ksplit <= ATT_KSMAX && c->batch > 0 &&
               attention_single_range(c, rows / c->batch)) {
             // the attention launch that follows sums the splits and applies the norm scale while it prepares its rows; only in
@@ -374,14 +374,15 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
             // C5 measured 2 % slower, C4 2 % faster)
             c->qkv_pending = QkvSrc{nullptr, 0, g.part, ksplit, g.M, g.ldp, g.ssp, g.n_parts, g.ssp_ld, 1.0f / (float)g.K, g.eps};
           } else {
-            hipLaunchKernelGGL((gemm_finish_kernel<EPI, NORM>), dim3((a.N / 4 + 255) / 256, g.M), dim3(256), 0, c->stream, g);
+            hipLaunchKernelGGL((gemm_finish_kernel<EPI, NORM>), dim3((a.N / 4 + 255) / 256, g.M), dim3(256), 0, c->stream,
+                               (const float*)g.part, (const float*)g.y, (const bf16_t*)g.g_next, g.ksplit, g.M, g.N, g.ldp, g.ldy, g);
           }
         }
       } else {
-        if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g);
-        else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g);
-        else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g);
-        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, false>), ggrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g);
+        if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+        else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+        else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, false>), ggrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
       }
     }
     return hipGetLastError();

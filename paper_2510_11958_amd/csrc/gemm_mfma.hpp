@@ -53,7 +53,11 @@ __device__ __forceinline__ void static_for(F&& f) {
 constexpr int gemm_waves(int cg, int epi) { return (cg >= 2 && epi != EPI_RESID && (cg <= 4 || epi == EPI_SWIGLU)) ? 8 : 4; }
 
 template <int EPI, bool NORM, int CG, bool SPLITK>
-__global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(MfmaArgs a) {
+__global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(
+    // what the prologue needs first, as leading scalars: they arrive in registers with the wave (kernel-argument preload), the
+    // struct's fields only after a load from the argument buffer (~1 us before the first weight could be requested)
+    const bf16_t* W_, const bf16_t* W2_, const bf16_t* xb_, const bf16_t* xb_lo_, int M_, int N_, int K_, int ldxb_, int ksplit_,
+    MfmaArgs a) {
   constexpr int GEMM_WAVES = gemm_waves(CG, EPI);
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
   // k-steps in flight: 3; 2 with 64 and more rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
@@ -70,20 +74,20 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, kg = lane >> 4;
-  const int M = a.M, N = a.N, K = a.K, KS = K >> 6;
+  const int M = M_, N = N_, K = K_, KS = K >> 6;
   const int n_tiles = (N + 15) >> 4;
   // this block's k-steps
-  const int s_lo = SPLITK ? (int)((long)blockIdx.y * KS / a.ksplit) : 0;
-  const int s_hi = SPLITK ? (int)((long)(blockIdx.y + 1) * KS / a.ksplit) : KS;
+  const int s_lo = SPLITK ? (int)((long)blockIdx.y * KS / ksplit_) : 0;
+  const int s_hi = SPLITK ? (int)((long)(blockIdx.y + 1) * KS / ksplit_) : KS;
 
   int tile[2];
   const bf16_t* wp[2];
   if (EPI == EPI_SWIGLU) {
     tile[0] = tile[1] = blockIdx.x * GEMM_WAVES + w;
-    wp[0] = a.W; wp[1] = a.W2;
+    wp[0] = W_; wp[1] = W2_;
   } else {
     tile[0] = (blockIdx.x * GEMM_WAVES + w) * 2; tile[1] = tile[0] + 1;
-    wp[0] = wp[1] = a.W;
+    wp[0] = wp[1] = W_;
   }
   const bool tv[2] = {tile[0] < n_tiles, tile[1] < n_tiles};
   const bf16_t* abase[2];
@@ -97,7 +101,7 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
 #pragma unroll
   for (int i = 0; i < PPT; ++i) {
     const int q = tid + i * NT, plane = q / (BM * 8), row = (q >> 3) % BM, c8 = q & 7;
-    bsrc[i] = (plane ? a.xb_lo : a.xb) + (size_t)min(row, M - 1) * a.ldxb + c8 * 8;
+    bsrc[i] = (plane ? xb_lo_ : xb_) + (size_t)min(row, M - 1) * ldxb_ + c8 * 8;
     bdst[i] = (plane * BM + row) * LDB + c8 * 8;
   }
 
@@ -296,12 +300,13 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(Mfm
 // Second stage of a K-split launch: out = epilogue(sum over the splits, in order).  One thread per
 // (activation row m, 4 consecutive outputs); a block covers 1024 outputs of one row.
 template <int EPI, bool NORM>
-__global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
+__global__ void __launch_bounds__(256) gemm_finish_kernel(const float* part_, const float* res_, const bf16_t* g_next_, int ksplit_, int M_, int N_, int ldp_, int ldy_,
+                                                         MfmaArgs a) {     // leading scalars: see gemm_mfma_kernel
   __shared__ float red_s[4];
   __shared__ float rs_sh;
   const int m = blockIdx.y, tid = threadIdx.x;
   const int n0 = (blockIdx.x * 256 + tid) * 4;
-  const int N = a.N, M = a.M;
+  const int N = N_, M = M_;
   const bool act = n0 < N;      // N is a multiple of 16 on this path
   const int nc = act ? n0 : 0;  // inactive threads load (and drop) the row's first outputs: no load sits under a per-lane condition
   // Every load of the kernel is issued here, before the first wait: the splits' partial sums (a split beyond ksplit
@@ -310,15 +315,15 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
   float4 x[KSMAX], y[KSMAX];
 #pragma unroll
   for (int ks = 0; ks < KSMAX; ++ks) {
-    const float* p = a.part + ((size_t)(ks < a.ksplit ? ks : a.ksplit - 1) * M + m) * a.ldp + nc;
+    const float* p = part_ + ((size_t)(ks < ksplit_ ? ks : ksplit_ - 1) * M + m) * ldp_ + nc;
     x[ks] = *(const float4*)p;
     if (EPI == EPI_SWIGLU) y[ks] = *(const float4*)(p + N);
   }
   float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f);
   uint2 graw = make_uint2(0u, 0u);
   if (EPI == EPI_RESID) {
-    h4 = *(const float4*)(a.y + (size_t)m * a.ldy + nc);
-    graw = *(const uint2*)(a.g_next + nc);
+    h4 = *(const float4*)(res_ + (size_t)m * ldy_ + nc);
+    graw = *(const uint2*)(g_next_ + nc);
   }
   float rs = 1.f;
   if (NORM) {
@@ -334,13 +339,13 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(MfmaArgs a) {
   float v[4] = {0.f, 0.f, 0.f, 0.f}, v2[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ks = 0; ks < KSMAX; ++ks) {
-    if (ks < a.ksplit) {
+    if (ks < ksplit_) {
       v[0] += x[ks].x; v[1] += x[ks].y; v[2] += x[ks].z; v[3] += x[ks].w;
       if (EPI == EPI_SWIGLU) { v2[0] += y[ks].x; v2[1] += y[ks].y; v2[2] += y[ks].z; v2[3] += y[ks].w; }
     }
   }
-  for (int ks = KSMAX; ks < a.ksplit; ++ks) {      // more splits than fetched up front (unusual shapes): one at a time
-    const float* p = a.part + ((size_t)ks * M + m) * a.ldp + nc;
+  for (int ks = KSMAX; ks < ksplit_; ++ks) {      // more splits than fetched up front (unusual shapes): one at a time
+    const float* p = part_ + ((size_t)ks * M + m) * ldp_ + nc;
     const float4 xv = *(const float4*)p;
     v[0] += xv.x; v[1] += xv.y; v[2] += xv.z; v[3] += xv.w;
     if (EPI == EPI_SWIGLU) {
