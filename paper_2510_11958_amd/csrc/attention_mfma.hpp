@@ -215,12 +215,14 @@ __device__ __forceinline__ void attn_prepare_rows_mfma(
 // results meet in dynamic shared memory: NW * QV * HD floats (QV = the block's query vectors).
 template <int HD, int NW, bool FINAL>
 __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
-    QkvSrc qs, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
-    const float2* __restrict__ rope_tab, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
-    float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
-    int kps /* keys per range, a multiple of 16 * NW */, int n_splits, int qv_stride,
-    const DevState* st, int sel, int offset, int r_total, int do_append,
-    bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int ldo /* FINAL only */) {
+    // in order of first use: the leading 16 dwords of scalars arrive in registers with the wave (kernel-argument preload;
+    // an argument struct ends it, so QkvSrc comes last), the rest after a load from the argument buffer
+    bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int nh, int nkv, int s_max,
+    int kps /* keys per range, a multiple of 16 * NW */, int r_total,
+    const DevState* st, int sel, int offset, const void* __restrict__ q_gain, int n_splits,
+    const void* __restrict__ k_gain, const float2* __restrict__ rope_tab,
+    float* __restrict__ part_o, float* __restrict__ part_ml, float eps, int qv_stride, int do_append,
+    bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int ldo /* FINAL only */, QkvSrc qs) {
   constexpr int QVT = 16;
   constexpr int NT = 64 * NW;
   constexpr int KSTEPS = HD / 32;      // MFMA steps over d for the scores

@@ -509,9 +509,10 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
       if (ae != hipSuccess) return ae;
       big_lds = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_rg, cf.n_kv_heads, B), dim3(64 * NW), lds, c->stream, qs,
-                       w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
-                       cf.max_seq_len, cf.rms_eps, kps, 1, kMaxRows * gq, st, sel, offset, r, append, (bf16_t*)attn, (bf16_t*)attn_lo, qd);
+    hipLaunchKernelGGL(kern, dim3(n_rg, cf.n_kv_heads, B), dim3(64 * NW), lds, c->stream,
+                       kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, 1,
+                       w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, kMaxRows * gq, append,
+                       (bf16_t*)attn, (bf16_t*)attn_lo, qd, qs);
     return hipGetLastError();
   }
   constexpr int KPI = 64;
@@ -520,9 +521,10 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
   if (want_splits < 1) want_splits = 1;
   int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
   const int ns = (bucket + kps - 1) / kps;
-  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, 4, false>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), (size_t)4 * qv_max * HD * 4, c->stream, qs,
-                     w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
-                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append, (bf16_t*)nullptr, (bf16_t*)nullptr, 0);
+  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, 4, false>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), (size_t)4 * qv_max * HD * 4, c->stream,
+                     kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, ns,
+                     w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, kMaxRows * gq, append,
+                     (bf16_t*)nullptr, (bf16_t*)nullptr, 0, qs);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
                      cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
   return hipGetLastError();
