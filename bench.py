@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--n-late", type=int, default=0, help="override the workload's number of decoding layers")
     ap.add_argument("--n-early", type=int, default=0, help="ExDy variant: encoding layers the in-cycle tokens reuse (0 = plain method)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--cycles-per-call", type=int, default=8,
+                    help="cycles enqueued per dmtd_decode call, i.e. how often the host collects the tokens (the tau=1 leg "
+                         "collects after the same number of tokens); 0: one dmtd_decode_cycle call per cycle")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
     ap.add_argument("--counters-run", action="store_true",
@@ -93,28 +96,43 @@ def main():
         eng.set_n_early(n_early)
     t_setup = time.time() - t0
 
-    def run(tau_run, cycles, warm):
+    def run(tau_run, cycles, warm, per_call):
+        """Times exactly `cycles` cycles of tau_run tokens.  per_call > 0: dmtd_decode calls of up to per_call cycles, enqueued
+        as one piece of GPU work each, the host collecting the tokens at the end of a call; 0: one blocking
+        dmtd_decode_cycle call per cycle."""
         eng.reset()
         eng.prefill(prompts)
         eng.decode_cycle(tau_run, n_late)                 # finishes cycle 1 (tau-1 tokens); untimed
         for _ in range(warm):
             eng.decode_cycle(tau_run, n_late)
+        if per_call:
+            eng.decode(tau_run, n_late, tau_run)          # one untimed cycle through the entry point being timed
         torch.cuda.synchronize()
         ctx0 = eng.state()["n_tok"]
         t = time.perf_counter()
-        ntok = 0
-        for _ in range(cycles):
-            ntok += eng.decode_cycle(tau_run, n_late).shape[1] * B
+        ntok, left = 0, cycles
+        while left > 0:
+            if per_call:
+                c = min(left, per_call, 64 // tau_run)
+                ntok += eng.decode(tau_run, n_late, c * tau_run).shape[1] * B
+            else:
+                c = 1
+                ntok += eng.decode_cycle(tau_run, n_late).shape[1] * B
+            left -= c
         torch.cuda.synchronize()
         dt = time.perf_counter() - t
+        assert ntok == cycles * tau_run * B
         return ntok, dt, ctx0
 
-    ntok, dt, ctx0 = run(tau, K, W)
+    cpc = max(0, min(args.cycles_per_call, 64 // tau))
+    ntok, dt, ctx0 = run(tau, K, W, cpc)
     if args.counters_run:
         print(f"counters run done: {ntok} tokens", file=sys.stderr)
         return
     # tau = 1 on the same kernels, over the same number of tokens
-    ntok1, dt1, _ = run(1, K * tau, W * tau)
+    ntok1, dt1, _ = run(1, K * tau, W * tau, cpc * tau)
+    # the same cycles with one blocking call per cycle (the host between all cycles), for reference
+    ntok_pc, dt_pc, _ = run(tau, K, W, 0) if cpc else (ntok, dt, ctx0)
 
     # algorithmic bytes of the timed DMTD cycles (true per-step context)
     total_bytes = 0
@@ -162,7 +180,8 @@ def main():
         "dtype": "bf16" if sh.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": wl.name + ("" if (tau, n_late, B, n_early) == (wl.tau, wl.n_late, wl.batch, 0) else
                                           f" [run with tau={tau}, n_late={n_late}, n_early={n_early}, batch={B}]"), "tau": tau, "n_late": n_late, "n_early": n_early, "batch": B, "prompt_len": P,
-                   "context_at_start": ctx0, "graphs": not args.no_graphs},
+                   "context_at_start": ctx0, "graphs": not args.no_graphs, "cycles_per_call": cpc},
+        "one_call_per_cycle_tokens_per_s": round(ntok_pc / dt_pc, 2),
         "tau1_tokens_per_s": round(ntok1 / dt1, 2), "speedup_vs_tau1": round((ntok / dt) / (ntok1 / dt1), 4),
         "end_to_end": {"algorithmic_GB_per_cycle": round(total_bytes / K / 1e9, 4), "achieved_GBs": round(e2e_gbs, 1),
                        "frac_of_hbm_peak": round(e2e_gbs / HBM_PEAK_GBS, 4)},

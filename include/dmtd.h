@@ -124,6 +124,20 @@ int dmtd_decode_cycle(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t max_ne
                       const int32_t* forced_inputs, int32_t n_forced,
                       int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
 
+/* Cycles back to back (Sec. 2.2): exactly n_steps decode steps (1 <= n_steps <= 64), with the
+ * same steps, in the same order and with the same results as repeated dmtd_decode_cycle calls
+ * with max_new = the steps still to run - a full step wherever a cycle of tau tokens is
+ * complete, late-only steps otherwise - but enqueued as one piece of GPU work: the tokens are
+ * selected on the device, so the host is not needed between cycles and synchronises once, at
+ * the end of the call (a decode loop that looks at its tokens every few cycles only).  The call
+ * may end inside a cycle; the next call, of either kind, continues it.
+ * forced_inputs, out_tokens, out_stride (>= n_steps), n_emitted: as for dmtd_decode_cycle.
+ * Nothing runs unless all n_steps steps fit (all-or-nothing).
+ * Errors: as dmtd_decode_cycle; DMTD_EINVAL for n_steps outside [1, 64]. */
+int dmtd_decode(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t n_steps,
+                const int32_t* forced_inputs, int32_t n_forced,
+                int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
+
 /* Copy the logits (Eq. 5) of the most recent step: HOST float32 [batch, vocab],
  * out_elems >= batch * vocab.  Errors: DMTD_ESTATE before prefill, DMTD_ECAPACITY. */
 int dmtd_logits(dmtd_ctx* ctx, float* out, size_t out_elems);

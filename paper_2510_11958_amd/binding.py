@@ -59,6 +59,9 @@ def load_library():
     lib.dmtd_decode_cycle.restype = C.c_int
     lib.dmtd_decode_cycle.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
                                       P(C.c_int32), C.c_int32, P(C.c_int32)]
+    lib.dmtd_decode.restype = C.c_int
+    lib.dmtd_decode.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
+                                P(C.c_int32), C.c_int32, P(C.c_int32)]
     lib.dmtd_logits.restype = C.c_int
     lib.dmtd_logits.argtypes = [C.c_void_p, P(C.c_float), C.c_size_t]
     lib.dmtd_get_state.restype = C.c_int
@@ -196,6 +199,20 @@ class Engine:
         else:
             fp, nf = None, 0
         self._check(self.lib.dmtd_decode_cycle(self._h, tau, n_late, max_new, fp, nf, _i32p(out), stride, C.byref(n)))
+        return out[:, :n.value].copy()
+
+    def decode(self, tau: int, n_late: int, n_steps: int, forced=None) -> np.ndarray:
+        """``n_steps`` decode steps, cycles back to back, one host synchronisation; ``[batch, n_steps]`` argmax tokens."""
+        B = getattr(self, "_batch", 1)
+        stride = max(1, min(n_steps, 64))
+        out = np.empty((B, stride), np.int32)
+        n = C.c_int32(0)
+        if forced is not None:
+            f = np.ascontiguousarray(np.atleast_2d(np.asarray(forced)), dtype=np.int32)
+            fp, nf = _i32p(f), f.shape[1]
+        else:
+            fp, nf = None, 0
+        self._check(self.lib.dmtd_decode(self._h, tau, n_late, n_steps, fp, nf, _i32p(out), stride, C.byref(n)))
         return out[:, :n.value].copy()
 
     def logits(self) -> np.ndarray:

@@ -1163,21 +1163,42 @@ int dmtd_prefill_ragged(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32
   return prefill_impl(c, tokens, batch, prompt_len, lengths, n_late, first_tokens);
 }
 
-int dmtd_decode_cycle(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new, const int32_t* forced_inputs,
-                      int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
+// Decode steps of one call: plan (host only), enqueue everything on the stream, one copy of the emitted tokens and one
+// synchronisation at the end.  cycles: false = stop when the current cycle is complete (dmtd_decode_cycle); true = go on
+// with further cycles until n_steps steps have run (dmtd_decode).
+static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_steps, bool cycles, const int32_t* forced_inputs,
+                        int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
   if (!c) return DMTD_EINVAL;
   const dmtd_config& cf = c->cfg;
   if (n_emitted) *n_emitted = 0;
   if (!out_tokens || !n_emitted) { c->err = "null output pointer"; return DMTD_EINVAL; }
   if (tau > kMaxTau) { c->err = "tau above the supported maximum (64)"; return DMTD_EINVAL; }
   if (forced_inputs && n_forced < 1) { c->err = "forced_inputs given with n_forced < 1"; return DMTD_EINVAL; }
+  if (cycles && (n_steps < 1 || n_steps > kMaxTau)) { c->err = "n_steps must be in [1, 64]"; return DMTD_EINVAL; }
   const int f_stride = forced_inputs ? n_forced : 0;
   std::vector<Step> steps;
   int err = 0;
   std::string why;
-  if (!c->sched.plan(tau, n_late, max_new, kMaxTau, steps, err, why)) {
-    c->err = why;
-    return err == 1 ? DMTD_EINVAL : (err == 2 ? DMTD_ESTATE : DMTD_ECAPACITY);
+  if (!cycles) {
+    if (!c->sched.plan(tau, n_late, n_steps, kMaxTau, steps, err, why)) {
+      c->err = why;
+      return err == 1 ? DMTD_EINVAL : (err == 2 ? DMTD_ESTATE : DMTD_ECAPACITY);
+    }
+  } else {
+    // cycle after cycle on a copy of the host state (the plan of a cycle depends on where the one before it ended);
+    // nothing runs unless every cycle can be planned
+    Sched ahead = c->sched;
+    ahead.trace.clear();
+    std::vector<Step> one;
+    while ((int)steps.size() < n_steps) {
+      if (!ahead.plan(tau, n_late, n_steps - (int)steps.size(), kMaxTau, one, err, why)) {
+        c->err = why;
+        return err == 1 ? DMTD_EINVAL : (err == 2 ? DMTD_ESTATE : DMTD_ECAPACITY);
+      }
+      ahead.commit(one, n_late);
+      ahead.trace.clear();
+      steps.insert(steps.end(), one.begin(), one.end());
+    }
   }
   const int n = (int)steps.size();
   if (out_stride < n) { c->err = "out_stride smaller than the number of steps"; return DMTD_ECAPACITY; }
@@ -1222,6 +1243,16 @@ int dmtd_decode_cycle(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new,
   c->sched.commit(steps, n_late);
   *n_emitted = n;
   return DMTD_OK;
+}
+
+int dmtd_decode_cycle(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new, const int32_t* forced_inputs,
+                      int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
+  return decode_steps(c, tau, n_late, max_new, false, forced_inputs, n_forced, out_tokens, out_stride, n_emitted);
+}
+
+int dmtd_decode(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_steps, const int32_t* forced_inputs,
+                int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
+  return decode_steps(c, tau, n_late, n_steps, true, forced_inputs, n_forced, out_tokens, out_stride, n_emitted);
 }
 
 int dmtd_logits(dmtd_ctx* c, float* out, size_t out_elems) {

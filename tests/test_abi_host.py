@@ -261,3 +261,41 @@ def test_build_refuses_spilling_matrix_core_kernels():
     bad = spilling_mfma_kernels(remarks)
     assert len(bad) == 1 and "gemv_mfma_kernel" in bad[0] and "516" in bad[0]
     assert spilling_mfma_kernels("") == []
+
+
+@pytest.mark.parametrize("tau,n_steps,chunks", [(3, 7, (7,)), (3, 11, (4, 1, 6)), (1, 5, (2, 3)), (4, 64, (64,)), (2, 9, (3, 3, 3))])
+def test_cycles_back_to_back_schedule_like_single_cycle_calls(tau, n_steps, chunks):
+    """dmtd_decode (Sec. 2.2, cycles back to back) runs the steps repeated dmtd_decode_cycle calls would run: same
+    schedule trace (Fig. 3), same counters, same state, also when a call ends inside a cycle."""
+    a, b = dry(max_seq_len=128), dry(max_seq_len=128)
+    for e in (a, b):
+        e.prefill([[1, 2, 3, 4, 5]])
+    done = 0
+    while done < n_steps:                      # reference: one call per cycle
+        done += a.decode_cycle(tau, 2, max_new=n_steps - done).shape[1]
+    assert sum(chunks) == n_steps
+    for c in chunks:
+        assert b.decode(tau, 2, c).shape == (1, c)
+    assert a.state() == b.state() and a.trace() == b.trace()
+    # and the two kinds of call continue each other's cycles
+    a.decode(tau, 2, 2); b.decode_cycle(tau, 2, max_new=1); b.decode_cycle(tau, 2, max_new=1)
+    assert a.state() == b.state() and a.trace() == b.trace()
+
+
+def test_cycles_back_to_back_errors_leave_the_state_alone():
+    e = dry(max_seq_len=12)
+    e.prefill([[1, 2, 3, 4]])
+    before, tr = e.state(), e.trace()
+    for n_steps, code in [(0, pkg.DMTD_EINVAL), (65, pkg.DMTD_EINVAL), (9, pkg.DMTD_ECAPACITY)]:
+        with pytest.raises(pkg.DmtdError) as ex:
+            e.decode(3, 1, n_steps)            # 9 steps would pass max_seq_len in the third cycle: nothing may run
+        assert ex.value.code == code and e.state() == before and e.trace() == tr
+    with pytest.raises(pkg.DmtdError) as ex:
+        e.decode(0, 1, 2)
+    assert ex.value.code == pkg.DMTD_EINVAL
+    lib = pkg.load_library()
+    out = np.empty(4, np.int32); n = C.c_int32()
+    p = out.ctypes.data_as(C.POINTER(C.c_int32))
+    assert lib.dmtd_decode(e._h, 3, 1, 5, None, 0, p, 4, C.byref(n)) == pkg.DMTD_ECAPACITY      # out_stride < n_steps
+    assert e.state() == before
+    assert e.decode(3, 1, 8).shape == (1, 8) and e.state()["n_tok"] == 12

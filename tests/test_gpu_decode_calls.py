@@ -1,0 +1,100 @@
+"""GPU tests of dmtd_decode (Sec. 2.2: cycles back to back, one host synchronisation per call).
+
+(1) Against the oracle: every call's last step is compared (logits within the model's tolerance, token where the oracle's
+    margin allows), the steps in between by their tokens, on teacher-forced strings so that near-ties cannot fork the
+    two sides; KV caches at the end.
+(2) Against repeated dmtd_decode_cycle calls on a second engine: the same kernels run in the same order on the same
+    data, so tokens, logits and caches must be bit-identical - free-running (every token feeds the next step), with
+    several sequences, with sampling, through graphs and without.
+"""
+import numpy as np
+import pytest
+
+import dmtd_inputs as di
+import paper_2510_11958_amd as pkg
+from parity_util import MARGIN, Pair, engine_config, norm_err, top2_margin
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+
+SHAPES = {
+    # name: (shape, batch, prompt_len, tau, n_late, calls (steps per dmtd_decode call))
+    "f32_tau3": (di.ModelShape(3, 128, 4, 1, 128, 200, 130, dtype="fp32"), 1, 9, 3, 2, (7, 1, 6)),
+    "f32_batch3_tau4": (di.ModelShape(4, 64, 4, 2, 64, 96, 61, dtype="fp32"), 3, 6, 4, 2, (9, 4, 2)),
+    "f32_tau1": (di.ModelShape(3, 64, 2, 1, 64, 96, 50, dtype="fp32"), 2, 5, 1, 3, (5, 3)),
+    "bf16_tau3": (di.ModelShape(4, 256, 8, 2, 128, 512, 1000, dtype="bf16"), 2, 300, 3, 2, (8, 5)),
+    "bf16_rows": (di.ModelShape(3, 256, 4, 2, 64, 512, 700, dtype="bf16"), 6, 40, 4, 1, (11, 6)),
+}
+
+
+def forced_string(vocab, batch, prompts, total_len, seed=1001):
+    cont = di.make_continuation(vocab, batch, total_len, seed=seed)
+    return [np.concatenate([prompts[b], cont[b]])[:total_len] for b in range(batch)]
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_back_to_back_cycles_against_the_oracle(name):
+    sh, B, P, tau, n_late, calls = SHAPES[name]
+    blob = di.make_weight_blob(sh, seed=3)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=5)
+    total = P + sum(calls) + 1
+    toks = forced_string(sh.vocab, B, prompts, total)
+    p = Pair(sh, blob, total + 2, batch=B)
+    p.prefill(prompts)
+    tol = TOL_F32 if sh.dtype == "fp32" else TOL_BF16
+    worst, checked = 0.0, 0
+    for n in calls:
+        nt = p.eng.state()["n_tok"]
+        f = np.stack([toks[b][nt:nt + n] for b in range(B)])
+        out = p.eng.decode(tau, n_late, n, forced=f)
+        assert out.shape == (B, n)
+        z = p.eng.logits()
+        for b, o in enumerate(p.orcs):
+            n0 = len(o.step_logits)
+            done = 0
+            while done < n:                                     # the oracle cycle by cycle, same forced inputs
+                done += len(o.decode_cycle(tau, n_late, max_new=n - done, forced=f[b][done:].tolist()))
+            refs = o.step_logits[n0:]
+            assert len(refs) == n
+            for i, ref in enumerate(refs):                      # every step's token, where the oracle's margin allows
+                if top2_margin(ref.astype(np.float64)) > MARGIN:
+                    assert int(out[b, i]) == int(np.argmax(ref)), (b, i)
+                    checked += 1
+            worst = max(worst, norm_err(z[b], refs[-1].astype(np.float64)))
+            assert int(out[b, -1]) == int(np.argmax(z[b]))
+        s, o = p.eng.state(), p.orcs[0]
+        assert (s["n_tok"], s["n_front"], s["phase"]) == (o.n_tok, o.n_front, o.phase)
+    assert worst < tol, worst
+    assert checked > 0
+    p.compare_kv(1e-5 if sh.dtype == "fp32" else 2e-2)
+    print(f"{name}: worst {worst:.2e}, tokens checked {checked}")
+
+
+@pytest.mark.parametrize("use_graphs", [True, False])
+@pytest.mark.parametrize("name,sampling", [("f32_tau3", False), ("f32_batch3_tau4", True), ("bf16_tau3", False), ("bf16_rows", True)])
+def test_back_to_back_cycles_equal_single_cycle_calls_bit_for_bit(name, sampling, use_graphs):
+    sh, B, P, tau, n_late, calls = SHAPES[name]
+    blob = di.make_weight_blob(sh, seed=3)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=5)
+    total = P + sum(calls) + 4
+    engs = [pkg.Engine(engine_config(sh, total, B, use_graphs=use_graphs), blob) for _ in range(2)]
+    for e in engs:
+        if sampling:
+            e.set_sampling(0.8, 20, 1234)
+        e.prefill(prompts)
+    a, b = engs
+    for n in calls:                                             # free-running: every token is the next step's input
+        got = b.decode(tau, n_late, n)
+        want = []
+        while sum(w.shape[1] for w in want) < n:
+            want.append(a.decode_cycle(tau, n_late, max_new=n - sum(w.shape[1] for w in want)))
+        want = np.concatenate(want, axis=1)
+        assert np.array_equal(got, want)
+        assert np.array_equal(a.logits(), b.logits())
+        assert a.state() == b.state()
+    assert a.trace() == b.trace()
+    nt = a.state()["n_tok"]
+    for l in range(sh.n_layers):
+        for s in range(B):
+            assert np.array_equal(a.read_kv(l, s, nt), b.read_kv(l, s, nt))
