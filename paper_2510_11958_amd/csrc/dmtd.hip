@@ -125,6 +125,7 @@ struct dmtd_ctx {
   std::vector<LayerW> layers;
   std::vector<LayerSw> sw;
   std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
+  std::map<std::vector<int>, hipGraphExec_t> group_graphs;            // several steps in one graph (dmtd_decode)
   bool sampling = false;      // tokens are drawn (dmtd_set_sampling) instead of taken greedily
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
   int att_bucket = 512;       // attention launches: context bucket (multiple of 512) the key ranges are laid out for
@@ -849,6 +850,60 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
   return DMTD_OK;
 }
 
+// Several consecutive steps of one call as ONE graph (dmtd_decode): the steps of a cycle - a full step and the late-only
+// steps behind it - or, at tau = 1, up to kStepsPerGraph full steps.  Between two graph launches the GPU idles for ~8 us
+// (end of one graph to the first kernel of the next), three times per C3 cycle with a graph per step.  The steps of a
+// group share their attention launch shape (512-token context bucket, KV sharing), otherwise the group ends early.
+constexpr int kStepsPerGraph = 4;
+int run_steps_grouped(dmtd_ctx* c, const std::vector<Step>& steps, int tau, int n_late) {
+  const int n = (int)steps.size();
+  int i = 0;
+  while (i < n) {
+    choose_attention(c, steps[i].pos + 1);
+    const int bucket = c->att_bucket;
+    const bool share = c->share_kv;
+    int j = i + 1;
+    const int limit = tau > 1 ? tau : kStepsPerGraph;
+    while (j < n && j - i < limit && !(tau > 1 && steps[j].full)) {
+      choose_attention(c, steps[j].pos + 1);
+      if (c->att_bucket != bucket || c->share_kv != share) break;
+      ++j;
+    }
+    if (!c->cfg.use_graphs || j - i == 1) {
+      const int rc = run_step(c, steps[i], n_late);
+      if (rc != DMTD_OK) return rc;
+      i += 1;
+      continue;
+    }
+    std::vector<int> key = {n_late, c->sched.n_early, c->sampling ? 1 : 0, bucket, share ? 1 : 0};
+    for (int k = i; k < j; ++k) { key.push_back(steps[k].full ? 1 : 0); key.push_back(steps[k].rows); }
+    auto it = c->group_graphs.find(key);
+    if (it == c->group_graphs.end()) {
+      hipGraph_t graph = nullptr;
+      HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      hipError_t e = hipSuccess;
+      for (int k = i; k < j && e == hipSuccess; ++k) {
+        choose_attention(c, steps[k].pos + 1);
+        e = enqueue_step(c, steps[k].full, steps[k].rows, n_late);
+      }
+      hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
+      if (e != hipSuccess || e2 != hipSuccess) {
+        if (graph) (void)hipGraphDestroy(graph);
+        c->err = std::string("graph capture failed: ") + hipGetErrorString(e != hipSuccess ? e : e2);
+        return DMTD_EHIP;
+      }
+      hipGraphExec_t exec = nullptr;
+      hipError_t e3 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(graph);
+      if (e3 != hipSuccess) { c->err = std::string("hipGraphInstantiate: ") + hipGetErrorString(e3); return DMTD_EHIP; }
+      it = c->group_graphs.emplace(key, exec).first;
+    }
+    HIP_TRY(c, hipGraphLaunch(it->second, c->stream));
+    i = j;
+  }
+  return DMTD_OK;
+}
+
 // Prefill (Sec. 2.2): all prompt positions through all layers, in chunks of rows
 hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
   const dmtd_config& cf = c->cfg;
@@ -994,6 +1049,8 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
 void destroy_graphs(dmtd_ctx* c) {
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
   c->graphs.clear();
+  for (auto& kv : c->group_graphs) (void)hipGraphExecDestroy(kv.second);
+  c->group_graphs.clear();
 }
 
 }  // namespace
@@ -1220,8 +1277,12 @@ static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_step
     hipLaunchKernelGGL(begin_call_kernel, dim3(1), dim3(256), 0, c->stream, (DevState*)(c->ws + c->o.state),
                        (int*)(c->ws + c->o.tokens), cf.max_seq_len, fdev, nf, B);
     HIP_TRY(c, hipGetLastError());
-    for (const Step& s : steps) {
-      const int rc = run_step(c, s, n_late);
+    int rc = DMTD_OK;
+    if (cycles) rc = run_steps_grouped(c, steps, tau, n_late);
+    else
+      for (const Step& s : steps)
+        if ((rc = run_step(c, s, n_late)) != DMTD_OK) break;
+    {
       if (rc != DMTD_OK) {
         // device state may be ahead of the host's; resynchronise it to the host's unchanged view
         (void)hipStreamSynchronize(c->stream);
