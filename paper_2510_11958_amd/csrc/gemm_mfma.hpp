@@ -18,9 +18,10 @@
 //
 // Memory-level parallelism: a tile has 3 k-steps (6 KiB) in flight, so a projection with few tiles
 // (QKV 384, O and down 160 at 4B shapes) would keep only 1-2 MB in flight, far below what HBM needs
-// (about 12 MB).  Such launches split K over gridDim.y blocks; each stores its raw partial tile sums,
-// and gemm_finish_kernel adds them in order and runs the epilogue.  The LM head (thousands of tiles)
-// runs unsplit with the epilogue in this kernel.
+// (about 12 MB), on a fraction of the chip.  Such launches split K over gridDim.y blocks, as many as
+// give the launch about one block per CU (the launcher decides); each stores its raw partial tile
+// sums, and gemm_finish_kernel adds them in order and runs the epilogue.  The LM head (thousands of
+// tiles) runs unsplit with the epilogue in this kernel.
 #pragma once
 #include <type_traits>
 #include "gemv_mfma.hpp"
