@@ -341,7 +341,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
       const int cg = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : (g.M <= 64 ? 4 : 8));
       const int gw = gemm_waves(cg, EPI);                  // a wave owns 2 tiles (SwiGLU: the gate and up tile of one)
       const dim3 ggrid(EPI == EPI_SWIGLU ? (n_tiles + gw - 1) / gw : (n_tiles + 2 * gw - 1) / (2 * gw));
-      // K is split so that the launch has about one block per CU and no more (a second round of blocks costs more than
+      // K is split so that the launch has about one block per CU and no more (a partly filled second wave of blocks costs more than
       // it brings; measured at 4B shapes, 128 rows: QKV 288 blocks 32.4 us, 240 blocks 24.4 us; gate/up 152 blocks 50.0 us,
       // 228 blocks 42.4 us, 304 blocks 57.3 us; down 160 / 240 / 320 blocks 31.6 / 27.0 / 38.1 us); the LM head has
       // blocks enough without splitting
