@@ -3,9 +3,12 @@
 
 Workload: the Qwen3-4B-shaped batch-1 configuration (36 layers, 1024-token prompt, 512
 generated tokens, tau=3, n_late=8) with seeded synthetic weights and prompt.  A "step" is
-one decode cycle (one full pass + tau-1 late-only passes = tau tokens).  The same run also
-times tau=1 (ordinary decoding) on the same kernels, the dominant kernel on its own with
-HIP events (roofline), and the CPU oracle on a bounded sample (cpu_baseline).
+one decode cycle (one full pass + tau-1 late-only passes = tau tokens).  Cycles are enqueued
+several at a time (dmtd_decode; --cycles-per-call, default 8: the host collects the tokens
+after every 8 cycles) and the rate with one blocking call per cycle is reported beside it.
+The same run also times tau=1 (ordinary decoding) on the same kernels, the host collecting
+after as many tokens, the dominant kernel on its own with HIP events (roofline), and the CPU
+oracle on a bounded sample (cpu_baseline).
 Prints ONE JSON line.
 """
 import argparse
