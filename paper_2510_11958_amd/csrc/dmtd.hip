@@ -408,7 +408,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
         if (ae != hipSuccess) return ae;                                                                                  \
         big_lds = true;                                                                                                   \
       }                                                                                                                   \
-      hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g);        \
+      hipLaunchKernelGGL(kern, grid, dim3(64 * NWT_), lds, c->stream, g.W, g.W2, g.xb, g.xb_lo, (const float*)g.ssp, g.M, g.N, g.K, g.n_parts, g.ssp_ld, g); \
     } while (0)
     if constexpr (ROLL_NW > 0) DMTD_LAUNCH_MFMA(ROLL_NW * MATS);
     else if (nw == 2) DMTD_LAUNCH_MFMA(2 * MATS);

@@ -96,8 +96,8 @@ struct MfmaArgs {
 // leading scalar arguments of a kernel arrive in registers at wave launch, the struct through a load.
 template <int EPI, bool NORM, int PF, int NWT, bool ROLL = false>   // NWT: waves per block (all matrices)
 __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, const bf16_t* W2_,
-                                                             const bf16_t* xb_, const bf16_t* xb_lo_,
-                                                             int M_, int N_, int K_, MfmaArgs a) {
+                                                             const bf16_t* xb_, const bf16_t* xb_lo_, const float* ssp_,
+                                                             int M_, int N_, int K_, int n_parts_, int ssp_ld_, MfmaArgs a) {
   extern __shared__ float4 dyn_smem[];
   bf16_t* xs = (bf16_t*)dyn_smem;                        // [2 planes][M][K], then (NORM) M * n_parts floats
   constexpr int MATS = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -150,11 +150,11 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
   float ssr[NSS];
   const int ss_m = tid & 15, ss_p0 = tid >> 4;
   if (NORM) {
-    const float* sp = a.ssp + (ss_m < M ? ss_m : M - 1);
+    const float* sp = ssp_ + (ss_m < M ? ss_m : M - 1);
 #pragma unroll
     for (int j = 0; j < NSS; ++j) {
       const int p = ss_p0 + j * (NT / 16);
-      ssr[j] = sp[(size_t)(p < a.n_parts ? p : a.n_parts - 1) * a.ssp_ld];
+      ssr[j] = sp[(size_t)(p < n_parts_ ? p : n_parts_ - 1) * ssp_ld_];
     }
   }
   u32x4 A[PF][2];
@@ -188,9 +188,9 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
 #pragma unroll
       for (int j = 0; j < NSS; ++j) {
         const int p = ss_p0 + j * (NT / 16);
-        if (p < a.n_parts) ss_items[p * M + ss_m] = ssr[j];
+        if (p < n_parts_) ss_items[p * M + ss_m] = ssr[j];
       }
-      for (int p = ss_p0 + NSS * (NT / 16); p < a.n_parts; p += NT / 16) ss_items[p * M + ss_m] = a.ssp[(size_t)p * a.ssp_ld + ss_m];
+      for (int p = ss_p0 + NSS * (NT / 16); p < n_parts_; p += NT / 16) ss_items[p * M + ss_m] = ssp_[(size_t)p * ssp_ld_ + ss_m];
     }
   }
 #pragma unroll
@@ -207,7 +207,7 @@ __global__ void __launch_bounds__(64 * NWT) gemv_mfma_kernel(const bf16_t* W_, c
       const int c = t >> 4, j = t & 15;
       float s = 0.f;
       if (c < M) {
-        for (int p = j; p < a.n_parts; p += 16) s += ss_items[p * M + c];
+        for (int p = j; p < n_parts_; p += 16) s += ss_items[p * M + c];
       }
       ss_s[c][j] = s;
     }
