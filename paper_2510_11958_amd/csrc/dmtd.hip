@@ -124,7 +124,7 @@ struct dmtd_ctx {
   const bf16_t* lm_head_sw = nullptr;
   std::vector<LayerW> layers;
   std::vector<LayerSw> sw;
-  std::map<std::tuple<int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late, share_kv)
+  std::map<std::tuple<int, int, int, int, int>, hipGraphExec_t> graphs;   // (full, rows, n_late / n_early / sampling, bucket / share_kv, batch)
   std::map<std::vector<int>, hipGraphExec_t> group_graphs;            // several steps in one graph (dmtd_decode)
   bool sampling = false;      // tokens are drawn (dmtd_set_sampling) instead of taken greedily
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
@@ -828,7 +828,8 @@ int run_step(dmtd_ctx* c, const Step& s, int n_late) {
     HIP_TRY(c, enqueue_step(c, s.full, s.rows, n_late));
     return DMTD_OK;
   }
-  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late * 4096 + c->sched.n_early + (c->sampling ? (1 << 30) : 0), c->att_bucket * 2 + (c->share_kv ? 1 : 0));
+  // everything a captured step bakes in: grids and row counts follow from the batch, the attention launch shape from the context bucket
+  const auto key = std::make_tuple(s.full ? 1 : 0, s.rows, n_late * 4096 + c->sched.n_early + (c->sampling ? (1 << 30) : 0), c->att_bucket * 2 + (c->share_kv ? 1 : 0), c->batch);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     hipGraph_t graph = nullptr;
@@ -875,7 +876,7 @@ int run_steps_grouped(dmtd_ctx* c, const std::vector<Step>& steps, int tau, int 
       i += 1;
       continue;
     }
-    std::vector<int> key = {n_late, c->sched.n_early, c->sampling ? 1 : 0, bucket, share ? 1 : 0};
+    std::vector<int> key = {c->batch, n_late, c->sched.n_early, c->sampling ? 1 : 0, bucket, share ? 1 : 0};
     for (int k = i; k < j; ++k) { key.push_back(steps[k].full ? 1 : 0); key.push_back(steps[k].rows); }
     auto it = c->group_graphs.find(key);
     if (it == c->group_graphs.end()) {
