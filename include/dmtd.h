@@ -138,6 +138,26 @@ int dmtd_decode(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t n_steps,
                 const int32_t* forced_inputs, int32_t n_forced,
                 int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
 
+/* dmtd_decode_cycle for callers that cannot allocate or synchronise: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same steps, same kernels and same results as dmtd_decode_cycle, with these differences:
+ *  - forced_inputs_dev and out_tokens_dev are DEVICE buffers (int32 [batch, n_forced] and [batch, out_stride], row-major;
+ *    forced_inputs_dev may be NULL); nothing is copied to or from the host.  Forced ids outside the vocabulary cannot be
+ *    seen by the host and are clamped into it on the device.
+ *  - the call allocates nothing (no hipMalloc / hipFree, no graph instantiation, no staging copies) and does not
+ *    synchronise: it enqueues the steps' kernels on the context's stream, one by one (use_graphs is ignored), and returns;
+ *    out_tokens_dev and dmtd_logits are valid once the stream has reached the end of that work.
+ *  - the steps' partial results (attention key ranges, selection keys of the LM head, K-split sums of the tiled
+ *    projection kernel) live in a 16 MiB array the library holds on each GPU it runs on, not in the workspace.  A call
+ *    whose partial results need more (they grow with batch x refill rows per sequence; a 4B-shaped model at batch 1 and
+ *    tau <= 4 needs 4.1 MiB) is refused with DMTD_ECAPACITY before anything runs.  All contexts on one GPU share the
+ *    array: two such calls whose GPU work overlaps on one GPU race; calls ordered on one stream do not.
+ * n_emitted: HOST, the number of steps enqueued (at most tau).  The host-side state (dmtd_get_state) advances at once.
+ * After DMTD_EHIP (a launch failed) the device state is undefined: call dmtd_reset.
+ * Errors: as dmtd_decode_cycle, plus DMTD_ECAPACITY for the scratch limit. */
+int dmtd_decode_cycle_noalloc(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t max_new,
+                              const int32_t* forced_inputs_dev, int32_t n_forced,
+                              int32_t* out_tokens_dev, int32_t out_stride, int32_t* n_emitted);
+
 /* Copy the logits (Eq. 5) of the most recent step: HOST float32 [batch, vocab],
  * out_elems >= batch * vocab.  Errors: DMTD_ESTATE before prefill, DMTD_ECAPACITY. */
 int dmtd_logits(dmtd_ctx* ctx, float* out, size_t out_elems);

@@ -62,6 +62,9 @@ def load_library():
     lib.dmtd_decode.restype = C.c_int
     lib.dmtd_decode.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
                                 P(C.c_int32), C.c_int32, P(C.c_int32)]
+    lib.dmtd_decode_cycle_noalloc.restype = C.c_int
+    lib.dmtd_decode_cycle_noalloc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                              C.c_void_p, C.c_int32, P(C.c_int32)]
     lib.dmtd_logits.restype = C.c_int
     lib.dmtd_logits.argtypes = [C.c_void_p, P(C.c_float), C.c_size_t]
     lib.dmtd_get_state.restype = C.c_int
@@ -214,6 +217,29 @@ class Engine:
             fp, nf = None, 0
         self._check(self.lib.dmtd_decode(self._h, tau, n_late, n_steps, fp, nf, _i32p(out), stride, C.byref(n)))
         return out[:, :n.value].copy()
+
+    def decode_cycle_noalloc(self, tau: int, n_late: int, out_dev, max_new: int = 0, forced_dev=None) -> int:
+        """dmtd_decode_cycle without allocation or synchronisation: ``out_dev`` (torch int32 CUDA tensor ``[batch, stride]``)
+        receives the steps' tokens once the engine's stream has run the enqueued work, ``forced_dev`` (torch int32 CUDA
+        tensor ``[batch, n_forced]`` or None) holds the forced inputs.  Returns the number of steps enqueued."""
+        n = C.c_int32(0)
+        if forced_dev is not None:
+            assert forced_dev.is_cuda and forced_dev.dtype.itemsize == 4 and forced_dev.is_contiguous()
+            fp, nf = forced_dev.data_ptr(), forced_dev.shape[1]
+        else:
+            fp, nf = None, 0
+        assert out_dev.is_cuda and out_dev.dtype.itemsize == 4 and out_dev.is_contiguous()
+        self._check(self.lib.dmtd_decode_cycle_noalloc(self._h, tau, n_late, max_new, fp, nf, out_dev.data_ptr(),
+                                                       out_dev.shape[1], C.byref(n)))
+        return n.value
+
+    def synchronize(self):
+        """Wait for the engine's stream (after calls that do not synchronise themselves)."""
+        if getattr(self, "_stream", None) is not None:
+            self._stream.synchronize()
+        else:
+            import torch
+            torch.cuda.synchronize()
 
     def logits(self) -> np.ndarray:
         B = getattr(self, "_batch", 1)

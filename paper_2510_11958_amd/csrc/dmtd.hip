@@ -75,6 +75,30 @@ constexpr int kMfmaPFQkv = 5;        // the same for the QKV projection: shorter
 
 thread_local std::string g_create_error;
 
+// The library's own scratch for dmtd_decode_cycle_noalloc (callers that cannot allocate and hand over no workspace for
+// partial results).  One copy per GPU the library runs on, held until the process ends; every context on a GPU shares
+// it, so two such calls that overlap on one GPU race.  The name below is a host-side stand-in: the device address is
+// taken once per device with hipGetSymbolAddress (dmtd_create) and only that address is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch_for_current_device(char** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 struct LayerW {   // tensors of one layer inside the caller's blob
   const void *attn_norm, *q, *k, *v, *q_norm, *k_norm, *o, *mlp_norm, *gate, *up, *down;
 };
@@ -131,6 +155,16 @@ struct dmtd_ctx {
   int att_bucket = 512;       // attention launches: context bucket (multiple of 512) the key ranges are laid out for
   bool fold_qkv = false;      // run_layer: a K-split QKV launch may leave its finishing step to the attention launch that follows
   QkvSrc qkv_pending{};       // ... and says so here (part != nullptr) until that launch picks it up
+  // Scratch of the step kernels (partial results that live for one launch pair): the attention ranges' partial outputs
+  // and softmax statistics, the LM head's selection-key cells, the K-split partial sums of the tiled kernel.  They sit
+  // in the caller's workspace, except inside dmtd_decode_cycle_noalloc, which points them at the library's own array.
+  float* part_o = nullptr;
+  float* part_ml = nullptr;
+  unsigned long long* amax = nullptr;
+  float* gemm_part = nullptr;
+  int part_rows = 0;          // rows per sequence the partials are laid out for (stride between ranges: part_rows * query heads per KV head)
+  char* static_scratch = nullptr;   // this device's copy of the library's own scratch array (address taken at create)
+  std::vector<Step> plan_buf;       // dmtd_decode_cycle_noalloc: the call's steps (capacity reserved at create)
 };
 
 namespace {
@@ -311,6 +345,14 @@ bool attention_single_range(const dmtd_ctx* c, int r) {
   return (long)cf.n_kv_heads * c->batch * n_rg >= c->num_cus;
 }
 
+// Whether `rows` packed activation rows of width K (both planes, plus n_parts partial sums of squares per row) stay in
+// LDS for the one-tile-per-block kernel of an [N, K] projection (otherwise the LDS-tiled kernel takes them).
+bool mfma_rows_fit(const dmtd_ctx* c, int rows, int N, int K, int n_parts) {
+  if (rows > kMfmaRows) return false;
+  const size_t lds_rows = (size_t)rows * ((size_t)4 * K + (size_t)n_parts * 4);
+  return lds_rows <= ((N + 15) / 16 <= c->num_cus ? (size_t)120 * 1024 : (size_t)DMTD_FIT_SMALL_KB * 1024);
+}
+
 template <int EPI, bool NORM, int PF = kMfmaPF, int ROLL_NW = 0>
 hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   const int KS = a.K / 64;
@@ -324,8 +366,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   // The one-tile-per-block kernel keeps all rows (both planes) in LDS: comfortably (two blocks per CU) in general,
   // up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway.  Rows that do not
   // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to kGemmRows rows.
-  const size_t lds_rows = (size_t)(rows < kMfmaRows ? rows : kMfmaRows) * ((size_t)4 * a.K + (NORM ? (size_t)a.n_parts * 4 : 0));
-  const bool fits = rows <= kMfmaRows && a.ldxb == a.K && lds_rows <= ((int)grid.x <= c->num_cus ? (size_t)120 * 1024 : (size_t)DMTD_FIT_SMALL_KB * 1024);
+  const bool fits = a.ldxb == a.K && mfma_rows_fit(c, rows, a.N, a.K, NORM ? a.n_parts : 0);
   if (!fits) {
     const int n_tiles = (a.N + 15) / 16;
     for (int m0 = 0; m0 < rows; m0 += kGemmRows) {
@@ -362,7 +403,7 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
         if constexpr (EPI != EPI_LOGITS) {
           g.ksplit = ksplit;
           g.ldp = (EPI == EPI_SWIGLU ? 2 : 1) * a.N;
-          g.part = (float*)(c->ws + c->o.gemm_part);
+          g.part = c->gemm_part;
           const dim3 sgrid(ggrid.x, ksplit);
           if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
           else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
@@ -467,14 +508,14 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn
   if (want_splits < 1) want_splits = 1;
   int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
   const int ns = (bucket + kps - 1) / kps;
-  float* po = (float*)(c->ws + c->o.part_o);
-  float* pml = (float*)(c->ws + c->o.part_ml);
+  float* po = c->part_o;
+  float* pml = c->part_ml;
   const DevState* st = dev_state(c);
   hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
-                     cf.max_seq_len, cf.rms_eps, kps, ns, kMaxRows * gq, st, sel, offset, r, append);
+                     cf.max_seq_len, cf.rms_eps, kps, ns, c->part_rows * gq, st, sel, offset, r, append);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
-                     cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r);
 }
 
 // The matrix-core kernel (bf16 caches): one pass over K and V serves up to 16 query vectors per KV head.
@@ -493,8 +534,8 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
   const LayerW& w = c->layers[l];
   const int bucket = c->att_bucket;
   long per_split_blocks = (long)cf.n_kv_heads * B * n_rg;
-  float* po = (float*)(c->ws + c->o.part_o);
-  float* pml = (float*)(c->ws + c->o.part_ml);
+  float* po = c->part_o;
+  float* pml = c->part_ml;
   const DevState* st = dev_state(c);
   QkvSrc qs = c->qkv_pending;           // the QKV projection's unfinished partial sums, if it left them to this launch
   c->qkv_pending = QkvSrc{};
@@ -512,7 +553,7 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
     }
     hipLaunchKernelGGL(kern, dim3(n_rg, cf.n_kv_heads, B), dim3(64 * NW), lds, c->stream,
                        kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, 1,
-                       w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, kMaxRows * gq, append,
+                       w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, c->part_rows * gq, append,
                        (bf16_t*)attn, (bf16_t*)attn_lo, qd, qs);
     return hipGetLastError();
   }
@@ -524,10 +565,10 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
   const int ns = (bucket + kps - 1) / kps;
   hipLaunchKernelGGL((attn_split_mfma_kernel<HD, 4, false>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), (size_t)4 * qv_max * HD * 4, c->stream,
                      kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, ns,
-                     w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, kMaxRows * gq, append,
+                     w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, c->part_rows * gq, append,
                      (bf16_t*)nullptr, (bf16_t*)nullptr, 0, qs);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
-                     cf.n_q_heads, cf.n_kv_heads, kps, ns, kMaxRows * gq, st, sel, offset, r);
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r);
   return hipGetLastError();
 }
 
@@ -699,7 +740,7 @@ hipError_t head_logits(dmtd_ctx* c, const Rows& R, int n_rows, float* logits, un
 // a9: final RMSNorm + LM head + greedy selection for one row per sequence; then the step's bookkeeping
 hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int n_rows) {
   const dmtd_config& cf = c->cfg;
-  unsigned long long* amax = (unsigned long long*)(c->ws + c->o.amax);
+  unsigned long long* amax = c->amax;
   hipError_t e = head_logits(c, R, n_rows, (float*)(c->ws + c->o.logits), amax, cf.max_batch);
   if (e != hipSuccess) return e;
   if (c->sampling && write_tokens) {
@@ -1093,9 +1134,20 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   c->sched.max_seq_len = cfg->max_seq_len;
   c->packed = cfg->dtype == DMTD_DTYPE_BF16;
   c->ssp_ld = cfg->max_batch * kMaxRows;
+  c->plan_buf.reserve(kMaxTau + 1);
+  c->sched.trace.reserve((size_t)12 * cfg->max_seq_len + 64);        // at most 3 records of 4 per step: later steps never reallocate
   if (!cfg->dry_run) {
     c->wbase = (const char*)weights_dev;
     c->ws = (char*)workspace_dev;
+    c->part_o = (float*)(c->ws + lay.part_o);
+    c->part_ml = (float*)(c->ws + lay.part_ml);
+    c->amax = (unsigned long long*)(c->ws + lay.amax);
+    c->gemm_part = c->packed ? (float*)(c->ws + lay.gemm_part) : nullptr;
+    c->part_rows = kMaxRows;
+    {
+      hipError_t se = static_scratch_for_current_device(&c->static_scratch);
+      if (se != hipSuccess) { g_create_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(se); delete c; return DMTD_EHIP; }
+    }
     // carve the blob
     const size_t d = cfg->hidden, qd = (size_t)cfg->n_q_heads * cfg->head_dim, kd = (size_t)cfg->n_kv_heads * cfg->head_dim;
     const size_t ff = cfg->intermediate, hd = cfg->head_dim;
@@ -1276,7 +1328,7 @@ static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_step
       HIP_TRY(c, hipMemcpyAsync(fdev, fhost.data(), (size_t)B * nf * 4, hipMemcpyHostToDevice, c->stream));
     }
     hipLaunchKernelGGL(begin_call_kernel, dim3(1), dim3(256), 0, c->stream, (DevState*)(c->ws + c->o.state),
-                       (int*)(c->ws + c->o.tokens), cf.max_seq_len, fdev, nf, B);
+                       (int*)(c->ws + c->o.tokens), cf.max_seq_len, fdev, nf, nf, cf.vocab, B);
     HIP_TRY(c, hipGetLastError());
     int rc = DMTD_OK;
     if (cycles) rc = run_steps_grouped(c, steps, tau, n_late);
@@ -1315,6 +1367,90 @@ int dmtd_decode_cycle(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new,
 int dmtd_decode(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_steps, const int32_t* forced_inputs,
                 int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
   return decode_steps(c, tau, n_late, n_steps, true, forced_inputs, n_forced, out_tokens, out_stride, n_emitted);
+}
+
+int dmtd_decode_cycle_noalloc(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t max_new, const int32_t* forced_dev,
+                              int32_t n_forced, int32_t* out_tokens_dev, int32_t out_stride, int32_t* n_emitted) {
+  if (!c) return DMTD_EINVAL;
+  const dmtd_config& cf = c->cfg;
+  if (n_emitted) *n_emitted = 0;
+  if (!n_emitted || (!out_tokens_dev && !cf.dry_run)) { c->err = "null output pointer"; return DMTD_EINVAL; }
+  if (tau > kMaxTau) { c->err = "tau above the supported maximum (64)"; return DMTD_EINVAL; }
+  if (forced_dev && n_forced < 1) { c->err = "forced inputs given with n_forced < 1"; return DMTD_EINVAL; }
+  std::vector<Step>& steps = c->plan_buf;       // capacity reserved at create: planning allocates nothing
+  int err = 0;
+  std::string why;
+  if (!c->sched.plan(tau, n_late, max_new, kMaxTau, steps, err, why)) {
+    c->err = why;
+    return err == 1 ? DMTD_EINVAL : (err == 2 ? DMTD_ESTATE : DMTD_ECAPACITY);
+  }
+  const int n = (int)steps.size();
+  if (out_stride < n) { c->err = "out_stride smaller than the number of steps"; return DMTD_ECAPACITY; }
+  if (!cf.dry_run) {
+    const int B = c->batch, gq = cf.n_q_heads / cf.n_kv_heads;
+    const int nf = forced_dev ? (n_forced < n ? n_forced : n) : 0;
+    // what the steps' kernels need beyond the workspace's state: sized for this call, carved from the library's array
+    int max_rows = 1;
+    bool tiled = false;
+    const int d = cf.hidden, qd = cf.n_q_heads * cf.head_dim, ff = cf.intermediate, nqkv = qd + 2 * cf.n_kv_heads * cf.head_dim;
+    const int tiles_d = (d + 15) / 16;
+    for (const Step& s : steps) {
+      if (s.rows > max_rows) max_rows = s.rows;
+      const int rows = B * (s.rows < kMaxRows ? s.rows : kMaxRows);
+      if (c->packed)
+        for (int rr : {rows, B})
+          tiled = tiled || !mfma_rows_fit(c, rr, nqkv, d, tiles_d) || !mfma_rows_fit(c, rr, d, qd, 0) || !mfma_rows_fit(c, rr, ff, d, tiles_d) ||
+                  !mfma_rows_fit(c, rr, d, ff, 0) || !mfma_rows_fit(c, rr, cf.vocab, d, tiles_d);
+    }
+    if (max_rows > kMaxRows) max_rows = kMaxRows;
+    const size_t qv_stride = (size_t)max_rows * gq;
+    const size_t amax_b = align_up((size_t)AMAX_CELLS * cf.max_batch * 8, 256);
+    const size_t pml_b = align_up((size_t)B * cf.n_kv_heads * ATT_MAX_SPLITS * qv_stride * 2 * 4, 256);
+    const size_t po_b = align_up((size_t)B * cf.n_kv_heads * ATT_MAX_SPLITS * qv_stride * cf.head_dim * 4, 256);
+    size_t gp_b = 0;
+    if (tiled) {
+      size_t widest = 2 * (size_t)ff > (size_t)nqkv ? 2 * (size_t)ff : (size_t)nqkv;
+      if ((size_t)d > widest) widest = d;
+      const size_t rows_max = (size_t)B * max_rows < (size_t)kGemmRows ? (size_t)B * max_rows : (size_t)kGemmRows;
+      gp_b = align_up((size_t)kGemmMaxSplit * rows_max * widest * 4, 256);
+    }
+    if (amax_b + pml_b + po_b + gp_b > kStaticScratchBytes) {
+      c->err = "dmtd_decode_cycle_noalloc: this call's partial results (" + std::to_string((amax_b + pml_b + po_b + gp_b) >> 10) +
+               " KiB for batch " + std::to_string(B) + " with " + std::to_string(max_rows) + " rows per sequence) exceed the library's " +
+               std::to_string(kStaticScratchBytes >> 20) + " MiB scratch; use dmtd_decode_cycle";
+      return DMTD_ECAPACITY;
+    }
+    // the steps run eagerly on the context's stream with their scratch in the library's array
+    struct Saved { float *po, *pml, *gp; unsigned long long* amax; int rows; } saved{c->part_o, c->part_ml, c->gemm_part, c->amax, c->part_rows};
+    char* base = c->static_scratch;
+    c->amax = (unsigned long long*)base;
+    c->part_ml = (float*)(base + amax_b);
+    c->part_o = (float*)(base + amax_b + pml_b);
+    c->gemm_part = (float*)(base + amax_b + pml_b + po_b);
+    c->part_rows = max_rows;
+    // the array keeps the last call's contents: the selection-key cells must start at zero (a fill kernel, so that a
+    // caller may capture this call into a graph)
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(4), dim3(256), 0, c->stream, c->amax, AMAX_CELLS * cf.max_batch);
+    hipLaunchKernelGGL(begin_call_kernel, dim3(1), dim3(256), 0, c->stream, (DevState*)(c->ws + c->o.state),
+                       (int*)(c->ws + c->o.tokens), cf.max_seq_len, forced_dev, nf, n_forced, cf.vocab, B);
+    hipError_t e = hipGetLastError();
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+      choose_attention(c, steps[i].pos + 1);
+      e = enqueue_step(c, steps[i].full, steps[i].rows, n_late);
+    }
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL(emitted_to_rows_kernel, dim3(1), dim3(256), 0, c->stream, (const int*)(c->ws + c->o.emitted), out_tokens_dev, n, B, out_stride);
+      e = hipGetLastError();
+    }
+    c->part_o = saved.po; c->part_ml = saved.pml; c->gemm_part = saved.gp; c->amax = saved.amax; c->part_rows = saved.rows;
+    if (e != hipSuccess) {
+      c->err = std::string("dmtd_decode_cycle_noalloc: ") + hipGetErrorString(e);
+      return DMTD_EHIP;
+    }
+  }
+  c->sched.commit(steps, n_late);
+  *n_emitted = n;
+  return DMTD_OK;
 }
 
 int dmtd_logits(dmtd_ctx* c, float* out, size_t out_elems) {

@@ -105,15 +105,27 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // Start of a decode call: set the forced-input horizon and the step counter, and copy
 // caller-forced input tokens into the token history at the positions they will occupy.
-__global__ void begin_call_kernel(DevState* st, int* tokens, int s_max, const int* forced, int n_forced, int batch) {
+// forced: [batch, f_stride], the first n_forced entries of a row are used; ids are clamped into the vocabulary (the host
+// has checked them where it can see them; a caller's DEVICE buffer it cannot).
+__global__ void begin_call_kernel(DevState* st, int* tokens, int s_max, const int* forced, int n_forced, int f_stride, int vocab, int batch) {
   const int base = st->n_tok;
   for (int i = threadIdx.x; i < batch * n_forced; i += blockDim.x) {
     const int b = i / n_forced, j = i % n_forced;
     const int pos = base + seq_delta(st)[b] + j;
-    if (pos < s_max) tokens[(size_t)b * s_max + pos] = forced[i];
+    const int t = forced[(size_t)b * f_stride + j];
+    if (pos < s_max) tokens[(size_t)b * s_max + pos] = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   }
   __syncthreads();
   if (threadIdx.x == 0) { st->forced_until = base + n_forced; st->step_idx = 0; }
+}
+
+// out[b * out_stride + i] = emitted[i * batch + b]: the steps' tokens of a call, per sequence (DEVICE to DEVICE)
+__global__ void emitted_to_rows_kernel(const int* __restrict__ emitted, int* __restrict__ out, int n_steps, int batch, int out_stride) {
+  for (int i = threadIdx.x; i < n_steps * batch; i += blockDim.x) out[(size_t)(i % batch) * out_stride + i / batch] = emitted[i];
+}
+
+__global__ void zero_u64_kernel(unsigned long long* p, int n) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0ull;
 }
 
 __global__ void set_state_kernel(DevState* st, int n_tok, int n_front) {
