@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--counters-run", action="store_true",
                     help="short run for rocprofv3 --pmc: 64-token prompt, DMTD leg only, no kernel timing (counter "
                          "collection serialises every dispatch); prints no benchmark line")
+    ap.add_argument("--table3", action="store_true",
+                    help="the paper's speed-test grid instead of the benchmark line: batch 1, 2, 4, 8 x tau 1..4 at a 1024-token "
+                         "prompt, 1024 generated tokens per sequence, whole generation timed (decode steps only); prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies first (known traffic, to scale rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -82,6 +85,9 @@ def main():
         del src, dst
 
     wl = di.WORKLOADS[args.workload]
+    if args.table3:
+        table3(args, di, pkg, torch, np, wl)
+        return
     sh, B, P, tau, n_late = wl.shape, wl.batch, wl.prompt_len, wl.tau, wl.n_late
     tau, n_late, B = args.tau or tau, args.n_late or n_late, args.batch or B
     n_early = args.n_early
@@ -152,16 +158,24 @@ def main():
     rows_late = B
     reps = 10
     per = {}
-    for kind, r in (("gateup", rows), ("gateup", rows_late), ("down", rows), ("qkv", rows), ("oproj", rows), ("lmhead", B),
-                    ("attn", 1), ("attn", min(tau, 4))):
+    r_seq = min(tau, 4)
+    for kind, r in (("gateup", rows), ("gateup", rows_late), ("down", rows), ("down", rows_late), ("qkv", rows), ("qkv", rows_late),
+                    ("oproj", rows), ("oproj", rows_late), ("lmhead", B), ("attn", 1), ("attn", r_seq)):
         per[f"{kind}_m{r}"] = eng.time_kernel(kind, r, reps)
+    # the same kernel times summed over one cycle's launches (full step: front layers with the refill rows, late layers
+    # and LM head with one row per sequence; tau-1 late-only steps), to set beside ms_per_step
+    layer_full = sum(per[f"{k}_m{rows}"] for k in ("qkv", "oproj", "gateup", "down")) + per[f"attn_m{r_seq}"]
+    layer_late = sum(per[f"{k}_m{rows_late}"] for k in ("qkv", "oproj", "gateup", "down")) + per["attn_m1"]
+    n_front = sh.n_layers - n_late - n_early
+    kernel_us_cycle = (n_front * layer_full + (n_late + n_early) * layer_late + per[f"lmhead_m{B}"]
+                       + (tau - 1) * ((n_late + n_early) * layer_late + per[f"lmhead_m{B}"]))
     gu_bytes = 2 * sh.intermediate * sh.hidden * sh.elem_bytes + sh.hidden * sh.elem_bytes
     achieved = gu_bytes / (per[f"gateup_m{rows}"] * 1e-6) / 1e9
-    traffic = measured_traffic(args.workload)
+    traffic, traffic_source = measured_traffic(args.workload)
     kernel_name = "gemv_mfma_kernel<SWIGLU, NORM>" if rows <= 5 else "gemm_mfma_kernel<SWIGLU, NORM> (+ gemm_finish_kernel)"
     roofline = {"bound": "hbm", "kernel": f"{kernel_name} with {rows} rows (RMSNorm + gate/up + SwiGLU)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "bytes_per_launch": gu_bytes, "avg_launch_us": round(per[f"gateup_m{rows}"], 2),
                 "other_kernels_us": {k: round(v, 2) for k, v in per.items()}}
     if rows > 16:
@@ -174,7 +188,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(di, blob, sh, tau, n_late)
+        cpu = cpu_baseline(di, blob, sh, tau, n_late, P)
 
     out = {
         "metric": "decode tokens/sec at 1 GPU (DMTD tau vs tau=1) + achieved HBM GB/s fraction",
@@ -188,23 +202,68 @@ def main():
         "tau1_tokens_per_s": round(ntok1 / dt1, 2), "speedup_vs_tau1": round((ntok / dt) / (ntok1 / dt1), 4),
         "end_to_end": {"algorithmic_GB_per_cycle": round(total_bytes / K / 1e9, 4), "achieved_GBs": round(e2e_gbs, 1),
                        "frac_of_hbm_peak": round(e2e_gbs / HBM_PEAK_GBS, 4)},
+        "kernel_us_sum_per_cycle": round(kernel_us_cycle, 1),
         "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(t_setup, 1),
     }
     print(json.dumps(out))
 
 
+def table3(args, di, pkg, torch, np, wl):
+    """The grid of the paper's speed test (Sec. 3.4, Table 3): 1024 random prompt tokens, 1024 generated tokens per
+    sequence, batch 1 / 2 / 4 / 8, ordinary decoding (tau = 1) and cycle lengths 2, 3, 4 with the last n_late layers
+    reused.  Timed: everything after prefill (the first token comes from prefill), i.e. 1023 decode steps' tokens per
+    sequence, through dmtd_decode calls of up to 64 steps; tokens/s = batch * 1023 / time."""
+    sh, n_late = wl.shape, args.n_late or wl.n_late
+    P, G = 1024, 1024
+    blob = di.make_weight_blob(sh, seed=0)
+    dev = torch.from_numpy(blob.view(np.int16)).cuda()
+    grid = {}
+    for B in (1, 2, 4, 8):
+        cfg = pkg.ModelConfig(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.intermediate, sh.vocab,
+                              dtype=sh.dtype, max_batch=B, max_seq_len=P + G + 8, use_graphs=not args.no_graphs)
+        eng = pkg.Engine(cfg, dev)
+        prompts = di.make_prompts(sh.vocab, B, P, seed=1)
+        for tau in (1, 2, 3, 4):
+            best = None
+            for rep in range(2):                      # the first pass also captures the graphs of every context bucket
+                eng.reset()
+                eng.prefill(prompts)
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                left = G - 1
+                while left > 0:
+                    n = min(left, 64 // tau * tau if left >= tau else left)
+                    left -= eng.decode(tau, n_late, n).shape[1]
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t
+                best = dt if best is None else min(best, dt)
+            assert eng.state()["n_tok"] == P + G - 1
+            grid[f"B{B}_tau{tau}"] = round(B * (G - 1) / best, 1)
+        eng.close()
+    out = {"table3": grid, "unit": "tokens/s", "prompt_len": P, "generated": G, "n_late": n_late,
+           "speedup_vs_tau1": {k: round(v / grid[k.split("_")[0] + "_tau1"], 3) for k, v in grid.items()},
+           "paper_speedup_batch1_a100": {"tau2": 1.44, "tau3": 1.85, "tau4": 2.15},
+           "workload": f"{wl.shape.n_layers}-layer 4B shape, P={P}, G={G}, n_late={n_late}, graphs {not args.no_graphs}"}
+    print(json.dumps(out))
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
-    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), or None."""
-    path = os.path.join(ROOT, "profiles", f"gateup_swiglu_{workload}_pmc.txt")
+    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), and where that figure comes
+    from: counters cannot be collected inside this run (collection serialises every dispatch), so the figure is the
+    one of the last counter run of this kernel, named with its commit and date.  (None, None) if there is none."""
+    rel = os.path.join("profiles", f"gateup_swiglu_{workload}_pmc.txt")
     try:
-        with open(path) as f:
-            return json.load(f)["traffic_bytes_per_launch"]
+        with open(os.path.join(ROOT, rel)) as f:
+            d = json.load(f)
+        run = d.get("counter_run", {})
+        return d["traffic_bytes_per_launch"], {"file": rel, "commit": run.get("commit"), "date": run.get("date"),
+                                               "measured_in_this_run": False}
     except Exception:
-        return None
+        return None, None
 
 
-def cpu_baseline(di, blob, sh, tau, n_late):
+def cpu_baseline(di, blob, sh, tau, n_late, prompt_len):
     """The NumPy oracle, as it stands, on this machine's host cores: decode tokens/s on a bounded sample."""
     import numpy as np
     from oracle import dmtd_oracle as O
@@ -218,20 +277,21 @@ def cpu_baseline(di, blob, sh, tau, n_late):
     big = di.blob_elems(sh) > 1_000_000_000
     dt = np.float32 if big else np.float64
     w = O.unpack_weights(blob, ocfg, dt)
-    P = 16
-    orc = O.DmtdOracle(ocfg, w, 64, dt)
-    orc.prefill(di.make_prompts(sh.vocab, 1, P, seed=1)[0])
+    P = min(prompt_len, 1024)      # the workload's own context where the oracle's (untimed) prefill stays within ~10 s
+    orc = O.DmtdOracle(ocfg, w, P + 64, dt)
+    orc.prefill(di.make_prompts(sh.vocab, 1, prompt_len, seed=1)[0][:P])
     orc.decode_cycle(tau, n_late)
     t = time.perf_counter()
     n = 0
     cycles = 0
-    while time.perf_counter() - t < 12.0 and orc.n_tok + tau < 60:
+    while time.perf_counter() - t < 12.0 and orc.n_tok + tau < P + 60:
         n += len(orc.decode_cycle(tau, n_late))
         cycles += 1
     el = time.perf_counter() - t
     return {"value": round(n / el, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{cycles} cycles of tau={tau}, n_late={n_late} after a {P}-token prompt (not the full prompt), "
-                      f"batch 1, oracle in {'float32' if big else 'float64'}"}
+            "sample": f"{cycles} cycles of tau={tau}, n_late={n_late} after a {P}-token prompt"
+                      f"{'' if P == prompt_len else f' (the first {P} tokens of the {prompt_len}-token prompt)'}, "
+                      f"batch 1 (one sequence of the workload), oracle in {'float32' if big else 'float64'}"}
 
 
 if __name__ == "__main__":

@@ -15,8 +15,14 @@
  *    only for the duration of a call.
  *  - All work is enqueued on the one HIP stream given at creation; calls that return
  *    host data synchronise that stream before returning.  A context is not thread-safe.
- *  - Every call returns 0 (DMTD_OK) or a negative code; a failed call leaves the
- *    context's state unchanged.  dmtd_last_error gives a message for the last failure.
+ *  - Every call returns 0 (DMTD_OK) or a negative code.  Arguments and state are checked
+ *    before anything is enqueued: a call that fails with DMTD_EINVAL, DMTD_ESTATE or
+ *    DMTD_ECAPACITY leaves the context's state unchanged, on the host and on the device.
+ *    After DMTD_EHIP (a launch, capture or copy failed midway) the host-side state and the
+ *    device's position counters are those before the call, but token-history and cache
+ *    entries written by steps that did complete remain (forced input tokens included):
+ *    repeating the same call gives what it would have given without the failure; before
+ *    any other use call dmtd_reset.  dmtd_last_error gives a message for the last failure.
  *  - A batch of sequences shares one prompt length and one cycle phase.
  *  - Positions are 0-based absolute token positions.
  *
@@ -162,15 +168,19 @@ int dmtd_decode_cycle_noalloc(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_
  * out_elems >= batch * vocab.  Errors: DMTD_ESTATE before prefill, DMTD_ECAPACITY. */
 int dmtd_logits(dmtd_ctx* ctx, float* out, size_t out_elems);
 
-/* Scheduler state.  n_tok: tokens that have entered the late layers' caches; n_front:
+/* Scheduler state (Sec. 2.2).  n_tok: tokens that have entered the late layers' caches; n_front:
  * tokens in the front layers' caches (n_tok - n_front await refill); phase: tokens of
  * the current cycle already emitted; counters[4] (HOST int64): layers traversed by
  * token-emitting rows, layers traversed by refill rows, tokens emitted by decode
- * steps, decode steps that were full steps.  Any pointer may be NULL. */
+ * steps, decode steps that were full steps.  counters[0] / (counters[2] * n_layers) is the
+ * percentage of layers per token of Eq. 7 (over whole cycles: (L + (tau-1) L_d) / (tau L));
+ * counters[0] + counters[1] is the total load, that of ordinary decoding once every token is
+ * refilled (Sec. 2.2).  Any pointer may be NULL. */
 int dmtd_get_state(const dmtd_ctx* ctx, int32_t* n_tok, int32_t* n_front, int32_t* phase,
                    int64_t* counters);
 
-/* Schedule trace since the last reset: one record of 4 int32 per (pass, layer group):
+/* Schedule trace since the last reset, in the form of the walk-through of Fig. 3 (which tokens pass which layer group in
+ * which forward pass): one record of 4 int32 per (pass, layer group):
  * pass number (1 = prefill), group (0 = front layers; with n_early > 0: the thinking layers, 1 = late layers, 2 = encoding layers of the ExDy variant), first
  * position, number of consecutive positions.  buf: HOST, cap_records records.
  * n_records receives the total number available (which may exceed cap_records). */

@@ -37,7 +37,9 @@ design notes):
 
 Pins: the vanilla path is checked against the Hugging Face Qwen3 implementation and
 against an independent brute-force recompute; the cycle machine against the one-shot
-masked forward, the Fig. 3 walk-through and Eq. 7.  Exact logit values for the seeded
+masked forward, the Fig. 3 walk-through and Eq. 7 (its ExDy form against cycles counted by hand);
+the ExDy variant and the literal reading of Eq. 4 against the Hugging Face model where the
+layers above them are made the identity.  Exact logit values for the seeded
 benchmark models are printed nowhere in the paper: those values are **parity
 unpinned** by the paper and rest on the pins above.
 """

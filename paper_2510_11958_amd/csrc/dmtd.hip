@@ -163,6 +163,7 @@ struct dmtd_ctx {
   unsigned long long* amax = nullptr;
   float* gemm_part = nullptr;
   int part_rows = 0;          // rows per sequence the partials are laid out for (stride between ranges: part_rows * query heads per KV head)
+  int test_fail_step = -1;    // tests of the failure path: the next decode call reports a launch failure before this step (once)
   char* static_scratch = nullptr;   // this device's copy of the library's own scratch array (address taken at create)
   std::vector<Step> plan_buf;       // dmtd_decode_cycle_noalloc: the call's steps (capacity reserved at create)
 };
@@ -1134,6 +1135,7 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   c->sched.max_seq_len = cfg->max_seq_len;
   c->packed = cfg->dtype == DMTD_DTYPE_BF16;
   c->ssp_ld = cfg->max_batch * kMaxRows;
+  if (const char* ev = std::getenv("DMTD_TEST_FAIL_STEP")) c->test_fail_step = std::atoi(ev);
   c->plan_buf.reserve(kMaxTau + 1);
   c->sched.trace.reserve((size_t)12 * cfg->max_seq_len + 64);        // at most 3 records of 4 per step: later steps never reallocate
   if (!cfg->dry_run) {
@@ -1331,7 +1333,13 @@ static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_step
                        (int*)(c->ws + c->o.tokens), cf.max_seq_len, fdev, nf, nf, cf.vocab, B);
     HIP_TRY(c, hipGetLastError());
     int rc = DMTD_OK;
-    if (cycles) rc = run_steps_grouped(c, steps, tau, n_late);
+    if (c->test_fail_step >= 0) {
+      // failure injected from the host (DMTD_TEST_FAIL_STEP at create): the steps before it run, then the call fails the
+      // way a refused launch would; every kernel that was enqueued completes normally
+      for (int i = 0; i < n && i < c->test_fail_step && rc == DMTD_OK; ++i) rc = run_step(c, steps[i], n_late);
+      if (rc == DMTD_OK) { c->err = "injected launch failure (DMTD_TEST_FAIL_STEP)"; rc = DMTD_EHIP; }
+      c->test_fail_step = -1;
+    } else if (cycles) rc = run_steps_grouped(c, steps, tau, n_late);
     else
       for (const Step& s : steps)
         if ((rc = run_step(c, s, n_late)) != DMTD_OK) break;

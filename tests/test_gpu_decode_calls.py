@@ -98,3 +98,41 @@ def test_back_to_back_cycles_equal_single_cycle_calls_bit_for_bit(name, sampling
     for l in range(sh.n_layers):
         for s in range(B):
             assert np.array_equal(a.read_kv(l, s, nt), b.read_kv(l, s, nt))
+
+
+@pytest.mark.parametrize("entry", ["decode_cycle", "decode"])
+def test_a_failed_call_can_be_repeated(entry, monkeypatch):
+    """The error path of a decode call (a launch that fails midway, here injected from the host before step 2 of the call:
+    the two steps before it run to completion on the GPU): the call reports DMTD_EHIP, the scheduler state on the host
+    is unchanged, and repeating the call gives tokens, logits and caches bit-identical to an engine that never failed."""
+    sh = di.ModelShape(4, 256, 8, 2, 128, 512, 1000, dtype="bf16")
+    B, P, tau, n_late = 2, 40, 4, 2
+    blob = di.make_weight_blob(sh, seed=3)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=5)
+    toks = forced_string(sh.vocab, B, prompts, P + 24)
+    good = pkg.Engine(engine_config(sh, P + 24, B), blob)
+    monkeypatch.setenv("DMTD_TEST_FAIL_STEP", "2")
+    bad = pkg.Engine(engine_config(sh, P + 24, B), blob)
+    monkeypatch.delenv("DMTD_TEST_FAIL_STEP")
+    for e in (good, bad):
+        e.prefill(prompts)
+
+    def call(e, n, forced):
+        return e.decode(tau, n_late, n, forced=forced) if entry == "decode" else e.decode_cycle(tau, n_late, forced=forced)
+
+    f = np.stack([toks[b][P:P + 6] for b in range(B)])
+    n = 6 if entry == "decode" else tau - 1
+    before = bad.state()
+    with pytest.raises(pkg.DmtdError) as err:
+        call(bad, n, f)
+    assert err.value.code == pkg.DMTD_EHIP and "injected" in str(err.value)
+    assert bad.state() == before
+    for forced in (f, None, None):                       # the repeated call, then free-running calls
+        assert np.array_equal(call(bad, n, forced), call(good, n, forced))
+        assert np.array_equal(bad.logits(), good.logits())
+        assert bad.state() == good.state()
+    nt = good.state()["n_tok"]
+    for l in range(sh.n_layers):
+        for b in range(B):
+            assert np.array_equal(bad.read_kv(l, b, nt), good.read_kv(l, b, nt))
+    assert bad.trace() == good.trace()

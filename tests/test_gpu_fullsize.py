@@ -89,12 +89,11 @@ def test_c3_full_prompt_first_cycles(model_4b):
         assert (s["n_tok"], s["n_front"], s["phase"]) == (orc.n_tok, orc.n_front, orc.phase)
     assert worst < TOL_BF16, worst
     # Cache contents of the first and the last layer against the oracle's unrounded float32 cache.
-    # Layer 0 carries one bf16 rounding of the stored value plus those of the projection's inputs.
-    # The last layer carries the noise of the 35 bf16 layers before it (measured: it grows roughly with
-    # the square root of the depth, evenly over positions); the maximum is taken over about a million
-    # entries (8 heads x 1032 positions x 128), whose extreme lies near five standard deviations, so
-    # the bounds are 3e-2 of the root mean square and 4e-2 of the largest entry.
-    for l, tol_rms, tol_max in ((0, 4e-3, 6e-3), (sh.n_layers - 1, 3e-2, 4e-2)):
+    # Layer 0 carries one bf16 rounding of the stored value (measured: 1.7e-3 of the root mean square, 3.3e-3 of
+    # the largest entry).  The last layer carries the noise of the bf16 caches of the 35 layers before it
+    # (measured: 9.8e-3 of the root mean square, 1.41e-2 of the largest entry for K, 1.06e-2 for V; it grows roughly
+    # with the square root of the depth, evenly over positions).  The bounds are 1.5 times the measured values.
+    for l, tol_rms, tol_max in ((0, 2.5e-3, 5e-3), (sh.n_layers - 1, 1.5e-2, 2.2e-2)):
         kv = eng.read_kv(l, 0, orc.n_tok)
         upto = orc.n_tok if l >= sh.n_layers - wl.n_late else orc.n_front
         for which, refc in ((0, orc.K[l]), (1, orc.V[l])):
@@ -102,6 +101,7 @@ def test_c3_full_prompt_first_cycles(model_4b):
             e = kv[which][:, :upto].astype(np.float64) - r
             e_rms = float(np.sqrt(np.mean(e * e)) / np.sqrt(np.mean(r * r)))
             e_max = float(np.abs(e).max() / np.abs(r).max())
+            print(f"C3 cache layer {l} {'KV'[which]}: e_rms {e_rms:.2e}, e_max {e_max:.2e}")
             assert e_rms < tol_rms and e_max < tol_max, (l, "KV"[which], e_rms, e_max)
     # whole-cycle calls, free running: tokens are the argmax of the logits the library reports
     for _ in range(6):

@@ -583,6 +583,100 @@ def test_exdy_schedule_counters_and_refill_span():
     assert late == [("enc", [o.n_tok - 1]), ("late", [o.n_tok - 1])]
 
 
+@pytest.mark.parametrize("literal", [False, True])
+def test_exdy_with_identity_upper_layers_equals_the_library_model_of_the_encoding_layers(literal):
+    """A pin of the ExDy variant outside the oracle: with W_o = W_d = 0 in every thinking and decoding layer those layers are
+    the identity, every token still passes the x encoding layers in its own step with its full causal context, and
+    h_masked = h_enc (Sec. 2.1, before Eq. 5), so the logits at EVERY position - full or inside a cycle - are those of
+    the Hugging Face Qwen3 model made of the encoding layers alone.  The plain method (x = 0) would give the LM head of
+    the raw embedding at in-cycle positions instead (pinned above).  Under the literal reading of Eq. 4 full positions
+    feed h_enc + h_think = 2 h_enc, which the final RMSNorm maps back up to its epsilon."""
+    x, y, tau, P, n = 2, 1, 3, 5, 20
+    _, cfg, w = make(full_pos_add_embed=literal)
+    for lw in w["layers"][x:]:
+        lw["o"] = np.zeros_like(lw["o"])
+        lw["down"] = np.zeros_like(lw["down"])
+    toks = di.make_prompts(TINY.vocab, 1, 24, seed=11)[0]
+    enc_only = dict(w, layers=w["layers"][:x])
+    m = hf_model(dataclasses.replace(TINY, n_layers=x), enc_only)
+    with torch.no_grad():
+        ref = m(torch.from_numpy(toks.astype(np.int64))[None]).logits[0].numpy()
+    o = run_forced_exdy(cfg, w, toks, P, tau, y, x, n)
+    assert len(o.step_logits) >= n - P + 1
+    in_cycle = 0
+    for i, z in enumerate(o.step_logits):                 # step i emits from position P - 1 + i
+        pos = P - 1 + i
+        tol = (2e-4 if literal else 5e-6) * np.abs(ref[pos]).max()
+        assert np.abs(z - ref[pos]).max() < tol, (pos, np.abs(z - ref[pos]).max())
+        in_cycle += (pos - (P - 1)) % tau != 0
+        # the plain method's in-cycle logits (LM head of the raw embedding) are far away: the pin can tell the two apart
+        E = w["embed"]
+        h = E[toks[pos]]
+        emb_only = E @ (h / math.sqrt(np.mean(h * h) + cfg.rms_eps) * w["final_norm"])
+        assert np.abs(emb_only - ref[pos]).max() > 1e-2 * np.abs(ref[pos]).max()
+    assert in_cycle >= 8
+
+
+def test_literal_eq4_with_identity_decoding_layers_against_the_library_hidden_state():
+    """A pin of the literal reading of Eq. 4 outside the oracle: with W_o = W_d = 0 in the decoding layers they are the
+    identity, so a full position's logits are E . norm(h_emb + h_think) with h_think the hidden state the Hugging Face
+    model reports after the front layers, and an in-cycle position's logits are E . norm(h_emb)."""
+    y, tau, P, n = 2, 3, 5, 20
+    F = TINY.n_layers - y
+    _, cfg, w = make(full_pos_add_embed=True)
+    for lw in w["layers"][F:]:
+        lw["o"] = np.zeros_like(lw["o"])
+        lw["down"] = np.zeros_like(lw["down"])
+    toks = di.make_prompts(TINY.vocab, 1, 24, seed=11)[0]
+    m = hf_model(TINY, w)
+    with torch.no_grad():
+        h_think = m(torch.from_numpy(toks.astype(np.int64))[None], output_hidden_states=True).hidden_states[F][0].numpy()
+    o = run_forced(cfg, w, toks, P, tau, y, n)
+    E = w["embed"]
+
+    def head(h):
+        return E @ (h / np.sqrt(np.mean(h * h) + cfg.rms_eps) * w["final_norm"])
+
+    n_full = n_in = 0
+    for i, z in enumerate(o.step_logits):
+        pos = P - 1 + i
+        full = (pos - (P - 1)) % tau == 0
+        want = head(E[toks[pos]] + h_think[pos]) if full else head(E[toks[pos]])
+        assert np.abs(z - want).max() < 5e-6 * np.abs(want).max(), (pos, full)
+        if full:                                          # and the default reading's value is far away
+            assert np.abs(head(h_think[pos]) - want).max() > 1e-2 * np.abs(want).max()
+        n_full += full
+        n_in += not full
+    assert n_full >= 4 and n_in >= 8
+
+
+def test_exdy_plt_against_hand_counted_cycles():
+    """Eq. 7 with L_d = x + y against layer counts written out by hand (tests/golden/plt_exdy_hand_count.txt): the
+    closed form, and the cycle machine's own counter on a model of that depth where it is small enough to run."""
+    n_rows = 0
+    for line in open(os.path.join(GOLDEN, "plt_exdy_hand_count.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        left, mid, right = [part.split() for part in line.split("|")]
+        L, x, y, tau = map(int, left)
+        per_token = list(map(int, mid))
+        num, den = map(int, right)
+        assert len(per_token) == tau and per_token[0] == L and all(v == x + y for v in per_token[1:])
+        assert sum(per_token) == num and den == tau * L
+        assert O.plt_closed_form(L, y, tau, x) == pytest.approx(num / den, abs=1e-15)
+        n_rows += 1
+        if L == 6:
+            _, cfg, w = make(SIX)
+            o = O.DmtdOracle(cfg, w, 64)
+            o.prefill([3, 1, 4, 1, 5])
+            o.decode_cycle(tau, y, n_early=x)                     # the rest of cycle 1
+            g0 = o.gen_layer_visits
+            for _ in range(3):
+                o.decode_cycle(tau, y, n_early=x)
+            assert o.gen_layer_visits - g0 == 3 * num
+    assert n_rows >= 8
+
+
 def test_exdy_state_errors():
     _, cfg, w = make(SIX)
     o = O.DmtdOracle(cfg, w, 64)
