@@ -23,7 +23,8 @@
  *    entries written by steps that did complete remain (forced input tokens included):
  *    repeating the same call gives what it would have given without the failure; before
  *    any other use call dmtd_reset.  dmtd_last_error gives a message for the last failure.
- *  - A batch of sequences shares one prompt length and one cycle phase.
+ *  - A batch of sequences shares one cycle phase (and, unless dmtd_prefill_ragged is used, one prompt length),
+ *    except through dmtd_decode_per_seq.
  *  - Positions are 0-based absolute token positions.
  *
  * Weight blob (DEVICE, element type per config.dtype, matrices row-major [out, in],
@@ -143,6 +144,30 @@ int dmtd_decode_cycle(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t max_ne
 int dmtd_decode(dmtd_ctx* ctx, int32_t tau, int32_t n_late, int32_t n_steps,
                 const int32_t* forced_inputs, int32_t n_forced,
                 int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
+
+/* Cycles per sequence (Sec. 2.2 applied to each sequence of a batch on its own; the evaluation of Sec. 3.7 varies the cycle
+ * length at inference): exactly n_steps decode steps (1 <= n_steps <= 64) in which sequence b decodes in cycles of tau[b]
+ * tokens, so the sequences of one batch may be at different points of their cycles - a sequence starts a new cycle (its
+ * pending tokens and its newest token pass the front layers, refilling its own front-layer KV entries) at the step after
+ * its own cycle is complete, whatever the others do.  In such a step the sequences that start a cycle pass the front layers
+ * (one weight pass per distinct number of pending rows among them), and ALL sequences' newest tokens then share one pass
+ * through the late layers and the LM head.  tau: HOST int32 [batch], each in [1, 64]; the lengths may change from call to
+ * call (a sequence whose cycle already holds tau[b] or more tokens starts a new one at the call's first step).
+ * forced_inputs, out_tokens, out_stride (>= n_steps), n_emitted: as for dmtd_decode.  All-or-nothing like dmtd_decode.
+ * While the sequences differ in phase or in pending tokens, dmtd_decode_cycle, dmtd_decode and dmtd_decode_cycle_noalloc
+ * return DMTD_ESTATE, dmtd_get_state reports sequence 0 (its counters[] follow sequence 0's schedule) and
+ * dmtd_get_seq_state any sequence; once they agree again the other calls work as before.  Not available in the ExDy
+ * variant (DMTD_ESTATE).
+ * Errors: DMTD_EINVAL, DMTD_ESTATE (no prefill; ExDy; n_late changed while tokens await refill), DMTD_ECAPACITY
+ * (max_seq_len, out_stride, more than 16 pending rows for a sequence), DMTD_EHIP. */
+int dmtd_decode_per_seq(dmtd_ctx* ctx, const int32_t* tau, int32_t n_late, int32_t n_steps,
+                        const int32_t* forced_inputs, int32_t n_forced,
+                        int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted);
+
+/* Scheduler state of sequence b after dmtd_decode_per_seq: n_front (in the coordinates of dmtd_get_state's n_tok, i.e.
+ * n_tok - n_front of its tokens await refill) and phase (tokens of its current cycle already emitted).  Either pointer may
+ * be NULL.  Errors: DMTD_EINVAL (b outside the batch). */
+int dmtd_get_seq_state(const dmtd_ctx* ctx, int32_t b, int32_t* n_front, int32_t* phase);
 
 /* dmtd_decode_cycle for callers that cannot allocate or synchronise: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same steps, same kernels and same results as dmtd_decode_cycle, with these differences:

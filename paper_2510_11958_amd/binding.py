@@ -62,6 +62,11 @@ def load_library():
     lib.dmtd_decode.restype = C.c_int
     lib.dmtd_decode.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
                                 P(C.c_int32), C.c_int32, P(C.c_int32)]
+    lib.dmtd_decode_per_seq.restype = C.c_int
+    lib.dmtd_decode_per_seq.argtypes = [C.c_void_p, P(C.c_int32), C.c_int32, C.c_int32, P(C.c_int32), C.c_int32,
+                                        P(C.c_int32), C.c_int32, P(C.c_int32)]
+    lib.dmtd_get_seq_state.restype = C.c_int
+    lib.dmtd_get_seq_state.argtypes = [C.c_void_p, C.c_int32, P(C.c_int32), P(C.c_int32)]
     lib.dmtd_decode_cycle_noalloc.restype = C.c_int
     lib.dmtd_decode_cycle_noalloc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
                                               C.c_void_p, C.c_int32, P(C.c_int32)]
@@ -217,6 +222,28 @@ class Engine:
             fp, nf = None, 0
         self._check(self.lib.dmtd_decode(self._h, tau, n_late, n_steps, fp, nf, _i32p(out), stride, C.byref(n)))
         return out[:, :n.value].copy()
+
+    def decode_per_seq(self, taus, n_late: int, n_steps: int, forced=None) -> np.ndarray:
+        """``n_steps`` decode steps with one cycle length per sequence (``taus``); ``[batch, n_steps]`` argmax tokens."""
+        B = getattr(self, "_batch", 1)
+        t = np.ascontiguousarray(np.asarray(taus), dtype=np.int32)
+        if t.shape != (B,):
+            raise ValueError("one cycle length per sequence")
+        stride = max(1, min(n_steps, 64))
+        out = np.empty((B, stride), np.int32)
+        n = C.c_int32(0)
+        if forced is not None:
+            f = np.ascontiguousarray(np.atleast_2d(np.asarray(forced)), dtype=np.int32)
+            fp, nf = _i32p(f), f.shape[1]
+        else:
+            fp, nf = None, 0
+        self._check(self.lib.dmtd_decode_per_seq(self._h, _i32p(t), n_late, n_steps, fp, nf, _i32p(out), stride, C.byref(n)))
+        return out[:, :n.value].copy()
+
+    def seq_state(self, b: int):
+        f, ph = C.c_int32(), C.c_int32()
+        self._check(self.lib.dmtd_get_seq_state(self._h, b, C.byref(f), C.byref(ph)))
+        return {"n_front": f.value, "phase": ph.value}
 
     def decode_cycle_noalloc(self, tau: int, n_late: int, out_dev, max_new: int = 0, forced_dev=None) -> int:
         """dmtd_decode_cycle without allocation or synchronisation: ``out_dev`` (torch int32 CUDA tensor ``[batch, stride]``)

@@ -184,7 +184,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
     const float2* __restrict__ rope_tab /* [s_max][HD / 2] (cos, sin) of position * theta^(-2i/HD) */, CT* __restrict__ kc, CT* __restrict__ vc,
     float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
     int kps /* keys per range, a multiple of the block iteration */, int n_splits, int qv_stride,
-    const DevState* st, int sel, int offset, int r_total, int do_append /* 0: leave the cache untouched (measurement) */) {
+    const DevState* st, int sel, int offset, int r_total, int do_append /* 0: leave the cache untouched (measurement) */,
+    const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot (cache rows, positions) */) {
   typedef typename Elem<CT>::Raw Raw;
   constexpr int LPK = HD / 8;          // lanes per key (16 or 8)
   constexpr int GPW = 64 / LPK;        // lane groups per wave (4 or 8)
@@ -196,6 +197,11 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
   constexpr int NEW_MAX = 16;          // rows a launch can carry
 
   const int g = blockIdx.y, b = blockIdx.z;
+  // rows and partials are indexed by the launch's sequence number b, the cache and the positions by the sequence's slot:
+  // the cache pointers are moved so that index b lands on the slot
+  const int bs = fmap ? fmap[b] : b;
+  kc += (ptrdiff_t)(bs - b) * nkv * s_max * HD;
+  vc += (ptrdiff_t)(bs - b) * nkv * s_max * HD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int GQ = nh / nkv;
   const int rpb = QVT / GQ;                                    // rows per block
@@ -226,7 +232,7 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
   };
   load_kv(key_begin, min(s_max, key_begin + kps));
 
-  const int pos_first = row_base(st, sel, offset, b);
+  const int pos_first = row_base(st, sel, offset, bs);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
   const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
@@ -310,7 +316,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
 template <int HD, typename OT>   // OT: float, or bf16_t (the packed input of the O projection: high parts to out, low parts to out_lo)
 __global__ void __launch_bounds__(256) attn_merge_kernel(
     const float* __restrict__ part_o, const float* __restrict__ part_ml, OT* __restrict__ out, OT* __restrict__ out_lo, int ldo,
-    int nh, int nkv, int kps, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total) {
+    int nh, int nkv, int kps, int n_splits, int qv_stride, const DevState* st, int sel, int offset, int r_total,
+    const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot (positions) */) {
   constexpr int T4 = HD / 4;              // threads per group: one per 4 consecutive d
   constexpr int NG = 256 / T4;            // groups (8 or 16); group sg takes ranges sg, sg + NG, ...
   constexpr int PRE = 4;                  // ranges per thread fetched before anything is waited for (4 * NG >= 32 ranges)
@@ -339,7 +346,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(
     const int uc = sg + u * NG < n_splits ? u : 0;
     ov[u] = *(const f32x4*)(po + uc * po_step);
   }
-  const int pos_row = row_base(st, sel, offset, b) + i;    // row i sees keys 0 .. pos_row
+  const int pos_row = row_base(st, sel, offset, fmap ? fmap[b] : b) + i;    // row i sees keys 0 .. pos_row
   const int n_act = min(n_splits, pos_row / kps + 1);   // ranges that hold keys visible to row i; later ones hold stale partials
   if (tid < 64) {
     // the first wave holds one range per lane: maximum and weighted sum by shuffles (a fixed tree: deterministic)

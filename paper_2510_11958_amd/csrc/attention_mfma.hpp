@@ -219,7 +219,8 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
     // an argument struct ends it, so QkvSrc comes last), the rest after a load from the argument buffer
     bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int nh, int nkv, int s_max,
     int kps /* keys per range, a multiple of 16 * NW */, int r_total,
-    const DevState* st, int sel, int offset, const void* __restrict__ q_gain, int n_splits,
+    const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot (cache rows, positions) */,
+    const DevState* st, int sel, int offset, int n_splits, const void* __restrict__ q_gain,
     const void* __restrict__ k_gain, const float2* __restrict__ rope_tab,
     float* __restrict__ part_o, float* __restrict__ part_ml, float eps, int qv_stride, int do_append,
     bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int ldo /* FINAL only */, QkvSrc qs) {
@@ -231,6 +232,11 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
   typedef unsigned int vraw_t __attribute__((ext_vector_type(DPL / 2)));   // DPL bf16 values
 
   const int g = blockIdx.y, b = blockIdx.z;
+  // rows and partials are indexed by the launch's sequence number b, the cache and the positions by the sequence's slot:
+  // the cache pointers are moved so that index b lands on the slot (no load, no wait, when there is no map)
+  const int bs = fmap ? fmap[b] : b;
+  kc += (ptrdiff_t)(bs - b) * nkv * s_max * HD;
+  vc += (ptrdiff_t)(bs - b) * nkv * s_max * HD;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int GQ = nh / nkv;
   const int rpb = QVT / GQ;                                    // rows per block
@@ -271,7 +277,7 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
   // the block's query vectors do not depend on the positions: fetched now, next to K and V
   const AttQueryPre<HD> qpre = attn_preload_query<HD>(qs, (const bf16_t*)q_gain, b, g, GQ, r_total, rg * rpb, QV, tid);
 
-  const int pos_first = row_base(st, sel, offset, b);
+  const int pos_first = row_base(st, sel, offset, bs);
   const int pos0 = pos_first + rg * rpb;                        // position of this block's first row
   const int ctx = pos0 + r;                                     // keys 0 .. ctx-1 are visible to its last row
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)

@@ -10,6 +10,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstdio>
@@ -31,6 +32,8 @@ constexpr int kMaxTau = 64;          // steps per decode call (size of the emitt
 constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming pass
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
 constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
+constexpr int kMaxPatterns = 64;     // distinct step patterns (which sequences start a cycle, with how many rows) a context keeps on the device
+constexpr size_t kPatternStride(size_t max_batch) { return (max_batch * 5 + 255) / 256 * 256; }   // int list [max_batch] + byte mask [max_batch]
 constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
 #ifndef DMTD_GEMM_MAXSPLIT
 #define DMTD_GEMM_MAXSPLIT 12
@@ -112,6 +115,7 @@ struct Ws {   // device workspace carve-up (byte offsets)
   size_t tokens, emitted, forced, state, inv_freq, rope_tab;
   size_t xb, xb_late, ssp, ssp_late, wsw;      // packed path only
   size_t gemm_part;                            // K-split partial sums of the tiled kernel
+  size_t patterns;
   size_t pend_enc, enc_tmp;                    // ExDy: stored encoding outputs of pending tokens; of a prefill chunk
   size_t mask, logits_rows, amax_rows, nll, best, loss;   // whole-sequence masked forward: mask, a chunk's logits and keys, per-position results
   size_t total;
@@ -153,6 +157,14 @@ struct dmtd_ctx {
   bool sampling = false;      // tokens are drawn (dmtd_set_sampling) instead of taken greedily
   bool share_kv = false;      // attention launches: one pass over K/V for all rows of a sequence (long contexts)
   int att_bucket = 512;       // attention launches: context bucket (multiple of 512) the key ranges are laid out for
+  const int* fmap = nullptr;  // launches of a front pass over SOME sequences: launch sequence -> sequence slot (device); null = all, in order
+  const unsigned char* full_mask = nullptr;   // the step's bookkeeping: which sequences close their refill gap (device); null = all or none
+  // sequences at different points of their cycles (dmtd_decode_per_seq): per-sequence phase and front position (in the
+  // counters' coordinates); while `diverged` the single-phase calls are refused
+  std::vector<int> seq_phase, seq_front;
+  bool diverged = false;
+  std::map<std::vector<int>, int> pattern_ids;      // rows per sequence of a step (0 = late-only) -> slot in the device pattern table
+  std::map<std::vector<int>, hipGraphExec_t> mixed_graphs;
   bool fold_qkv = false;      // run_layer: a K-split QKV launch may leave its finishing step to the attention launch that follows
   QkvSrc qkv_pending{};       // ... and says so here (part != nullptr) until that launch picks it up
   // Scratch of the step kernels (partial results that live for one launch pair): the attention ranges' partial outputs
@@ -227,7 +239,8 @@ Ws layout(const dmtd_config& c) {
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
   w.forced = take((size_t)kMaxTau * B * 4);
-  w.state = take(kStateDeltaOff + 8 * B);             // counters, sampling parameters, per-sequence position deltas and last prompt positions
+  w.state = take(kStateDeltaOff + 12 * B);            // counters, sampling parameters, per-sequence (delta, front position) pairs, last prompt positions
+  w.patterns = take((size_t)kMaxPatterns * kPatternStride(B));   // sequence lists and masks of steps whose sequences are at different points of their cycles
   w.inv_freq = take((hd / 2) * 8);
   w.pend_enc = take(B * kMaxTau * d * 4);
   w.enc_tmp = take(rows * d * 4);
@@ -514,9 +527,9 @@ void launch_attention_t(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn
   const DevState* st = dev_state(c);
   hipLaunchKernelGGL((attn_split_kernel<CT, HD, QVT>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), 0, c->stream, qkv, nqkv,
                      w.q_norm, w.k_norm, (const float2*)(c->ws + c->o.rope_tab), kc, vc, po, pml, cf.n_q_heads, cf.n_kv_heads,
-                     cf.max_seq_len, cf.rms_eps, kps, ns, c->part_rows * gq, st, sel, offset, r, append);
+                     cf.max_seq_len, cf.rms_eps, kps, ns, c->part_rows * gq, st, sel, offset, r, append, c->fmap);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
-                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r);
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r, c->fmap);
 }
 
 // The matrix-core kernel (bf16 caches): one pass over K and V serves up to 16 query vectors per KV head.
@@ -553,7 +566,7 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
       big_lds = true;
     }
     hipLaunchKernelGGL(kern, dim3(n_rg, cf.n_kv_heads, B), dim3(64 * NW), lds, c->stream,
-                       kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, 1,
+                       kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, c->fmap, st, sel, offset, 1, w.q_norm,
                        w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, c->part_rows * gq, append,
                        (bf16_t*)attn, (bf16_t*)attn_lo, qd, qs);
     return hipGetLastError();
@@ -565,11 +578,11 @@ hipError_t launch_attention_mfma_t(dmtd_ctx* c, int l, const float* qkv, OT* att
   int kps = ((bucket + want_splits - 1) / want_splits + KPI - 1) / KPI * KPI;
   const int ns = (bucket + kps - 1) / kps;
   hipLaunchKernelGGL((attn_split_mfma_kernel<HD, 4, false>), dim3(ns * n_rg, cf.n_kv_heads, B), dim3(256), (size_t)4 * qv_max * HD * 4, c->stream,
-                     kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, st, sel, offset, w.q_norm, ns,
+                     kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, kps, r, c->fmap, st, sel, offset, ns, w.q_norm,
                      w.k_norm, (const float2*)(c->ws + c->o.rope_tab), po, pml, cf.rms_eps, c->part_rows * gq, append,
                      (bf16_t*)nullptr, (bf16_t*)nullptr, 0, qs);
   hipLaunchKernelGGL((attn_merge_kernel<HD, OT>), dim3(r, cf.n_q_heads, B), dim3(256), 0, c->stream, po, pml, attn, attn_lo, qd,
-                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r);
+                     cf.n_q_heads, cf.n_kv_heads, kps, ns, c->part_rows * gq, st, sel, offset, r, c->fmap);
   return hipGetLastError();
 }
 
@@ -609,11 +622,11 @@ hipError_t embed_rows(dmtd_ctx* c, Rows& R, int sel, int offset, int r, int next
   if (c->packed) {
     hipLaunchKernelGGL(embed_pack_kernel, dim3(rows), dim3(256), 0, c->stream, (const bf16_t*)c->embed, dev_tokens(c),
                        cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h, (const bf16_t*)norm_gain_for_layer(c, next_layer),
-                       R.xb, R.xb_lo, R.ssp);
+                       R.xb, R.xb_lo, R.ssp, c->fmap);
     R.n_parts = 1;
   } else {
     hipLaunchKernelGGL(embed_kernel<float>, dim3(rows), dim3(256), 0, c->stream, (const float*)c->embed, dev_tokens(c),
-                       cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h);
+                       cf.max_seq_len, dev_state(c), sel, offset, r, cf.hidden, R.h, c->fmap);
   }
   return hipGetLastError();
 }
@@ -642,11 +655,11 @@ hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int ad
   if (c->packed) {
     hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden, add_embed,
                        (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset,
-                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp, (const float*)nullptr, last_pos);
+                       (const bf16_t*)norm_gain_for_layer(c, next_layer), dst.xb, dst.xb_lo, dst.ssp, (const float*)nullptr, last_pos, c->fmap);
     dst.n_parts = 1;
   } else {
     hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, src.h, dst.h, r, cf.hidden,
-                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, (const float*)nullptr, last_pos);
+                       add_embed, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), sel, offset, (const float*)nullptr, last_pos, c->fmap);
   }
   return hipGetLastError();
 }
@@ -750,7 +763,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(finish_step_kernel, dim3(1), dim3(n_rows >= 16 ? 1024 : 64 * n_rows), 0, c->stream, dev_state(c), amax, AMAX_CELLS, cf.max_batch,
-                     dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens);
+                     dev_tokens(c), (int*)(c->ws + c->o.emitted), cf.max_seq_len, n_rows, full, write_tokens, c->full_mask);
   return hipGetLastError();
 }
 
@@ -818,11 +831,11 @@ hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
           hipLaunchKernelGGL(take_last_pack_kernel, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden, 0,
                              (const bf16_t*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
                              (const bf16_t*)norm_gain_for_layer(c, F), late.xb, late.xb_lo, late.ssp,
-                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr);
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr, (const int*)nullptr);
         else
           hipLaunchKernelGGL(take_last_rows_kernel<float>, dim3(c->batch), dim3(256), 0, c->stream, front.h, late.h, rc, cf.hidden,
                              0, (const float*)c->embed, dev_tokens(c), cf.max_seq_len, dev_state(c), (int)POS_NFRONT, c0 - rc,
-                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr);
+                             cf.full_pos_add_embed ? (const float*)late.h : (const float*)nullptr, (const int*)nullptr, (const int*)nullptr);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         late.n_parts = 1;
       } else {
@@ -851,6 +864,39 @@ hipError_t enqueue_step(dmtd_ctx* c, bool full, int r, int n_late) {
   for (int l = F; l < cf.n_layers; ++l)
     if ((e = run_layer(c, l, late, 1, POS_NTOK, 0)) != hipSuccess) return e;
   return run_head(c, late, full ? 1 : 0, 1, c->batch);
+}
+
+// One decode step of a batch whose sequences are at different points of their cycles (Sec. 2.2, per sequence).  The
+// sequences that start a new cycle pass the front layers with their pending rows - one front pass per distinct row count,
+// over those sequences only (full_list: their slots, sorted by row count; n_rows / n_seqs: the groups) - and every
+// sequence's newest token then shares ONE pass through the late layers and the LM head: the late layers read the front
+// output for the former and the raw embedding for the others (Eq. 4).
+hipError_t enqueue_step_mixed(dmtd_ctx* c, const std::vector<std::pair<int, int>>& groups /* (rows, sequences) */, int n_late,
+                              const int* full_list, const unsigned char* full_mask) {
+  const dmtd_config& cf = c->cfg;
+  const int F = cf.n_layers - n_late, B = c->batch;
+  Rows front = front_rows(c), late = late_rows(c);
+  hipError_t e;
+  if ((e = embed_rows(c, late, POS_NTOK, 0, 1, F)) != hipSuccess) return e;
+  int first = 0;
+  for (const auto& grp : groups) {
+    const int r = grp.first, n = grp.second;
+    c->batch = n;
+    c->fmap = full_list + first;
+    e = embed_rows(c, front, POS_NFRONT, 0, r, 0);
+    for (int l = 0; l < F && e == hipSuccess; ++l) e = run_layer(c, l, front, r, POS_NFRONT, 0);
+    if (e == hipSuccess) e = take_last_rows(c, front, late, r, cf.full_pos_add_embed ? 1 : 0, POS_NFRONT, 0, F);
+    c->batch = B;
+    c->fmap = nullptr;
+    if (e != hipSuccess) return e;
+    first += n;
+  }
+  for (int l = F; l < cf.n_layers; ++l)
+    if ((e = run_layer(c, l, late, 1, POS_NTOK, 0)) != hipSuccess) return e;
+  c->full_mask = full_mask;
+  e = run_head(c, late, 0, 1, B);
+  c->full_mask = nullptr;
+  return e;
 }
 
 // K/V bytes one layer's attention reads for the whole batch at context length ctx
@@ -953,7 +999,7 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
   Rows front = front_rows(c), late = late_rows(c);
   const int add_at = cf.full_pos_add_embed ? cf.n_layers - n_late : -1;
   hipError_t e;
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, dev_state(c), P - 1, P - 1);
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, dev_state(c), P - 1, P - 1, cf.max_batch);
   int r_last = 0, p_last = 0;
   for (int p0 = 0; p0 < P; p0 += kPrefillChunk) {
     const int r = P - p0 < kPrefillChunk ? P - p0 : kPrefillChunk;
@@ -976,7 +1022,7 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
     r_last = r; p_last = p0;
     // prompts of different lengths: a sequence whose last prompt position lies in this chunk hands that row to the LM head
     if (ragged && (e = take_last_rows(c, front, late, r, 0, POS_EXPLICIT, p0, cf.n_layers,
-                                      (const int*)(c->ws + c->o.state + kStateDeltaOff) + cf.max_batch)) != hipSuccess) return e;
+                                      (const int*)(c->ws + c->o.state + kStateDeltaOff) + 2 * cf.max_batch)) != hipSuccess) return e;
   }
   if (!ragged && (e = take_last_rows(c, front, late, r_last, 0, POS_EXPLICIT, p_last, cf.n_layers)) != hipSuccess) return e;
   return run_head(c, late, 1, 1, c->batch);   // state goes from P-1 to n_tok = n_front = P
@@ -1094,6 +1140,8 @@ void destroy_graphs(dmtd_ctx* c) {
   c->graphs.clear();
   for (auto& kv : c->group_graphs) (void)hipGraphExecDestroy(kv.second);
   c->group_graphs.clear();
+  for (auto& kv : c->mixed_graphs) (void)hipGraphExecDestroy(kv.second);
+  c->mixed_graphs.clear();
 }
 
 }  // namespace
@@ -1181,7 +1229,7 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
       e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.amax, 0, (size_t)AMAX_CELLS * cfg->max_batch * 8, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, kStateDeltaOff + 8 * (size_t)cfg->max_batch, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.state, 0, kStateDeltaOff + 12 * (size_t)cfg->max_batch, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws + lay.kv, 0, lay.kv_layer_stride * cfg->n_layers, c->stream);
     if (e == hipSuccess && c->packed) {
       // one-time repack of every matrix into MFMA operand order (q, k, v are contiguous: one fused matrix)
@@ -1243,12 +1291,12 @@ static int prefill_impl(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32
     int* dtok = (int*)(c->ws + c->o.tokens);
     // padding behind a shorter prompt is replaced by token 0: those rows run (their results are never read) and must index the table safely
     std::vector<int32_t> tk(tokens, tokens + (size_t)batch * prompt_len);
-    std::vector<int32_t> meta(2 * (size_t)cf.max_batch, 0);       // delta[max_batch], last_prompt_pos[max_batch]
+    std::vector<int32_t> meta(3 * (size_t)cf.max_batch, 0);       // (delta, front)[max_batch], last_prompt_pos[max_batch]
     for (int b = 0; b < batch; ++b) {
       const int len = lengths ? lengths[b] : prompt_len;
       for (int i = len; i < prompt_len; ++i) tk[(size_t)b * prompt_len + i] = 0;
-      meta[b] = len - prompt_len;
-      meta[cf.max_batch + b] = len - 1;
+      meta[2 * b] = len - prompt_len;                            // the front positions are set by the prefill itself
+      meta[2 * cf.max_batch + b] = len - 1;
     }
     HIP_TRY(c, hipMemcpyAsync(c->ws + c->o.state + kStateDeltaOff, meta.data(), meta.size() * 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpy2DAsync(dtok, (size_t)cf.max_seq_len * 4, tk.data(), (size_t)prompt_len * 4, (size_t)prompt_len * 4, batch,
@@ -1287,6 +1335,7 @@ static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_step
   if (tau > kMaxTau) { c->err = "tau above the supported maximum (64)"; return DMTD_EINVAL; }
   if (forced_inputs && n_forced < 1) { c->err = "forced_inputs given with n_forced < 1"; return DMTD_EINVAL; }
   if (cycles && (n_steps < 1 || n_steps > kMaxTau)) { c->err = "n_steps must be in [1, 64]"; return DMTD_EINVAL; }
+  if (c->diverged) { c->err = "the sequences are at different points of their cycles: use dmtd_decode_per_seq"; return DMTD_ESTATE; }
   const int f_stride = forced_inputs ? n_forced : 0;
   std::vector<Step> steps;
   int err = 0;
@@ -1347,8 +1396,8 @@ static int decode_steps(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t n_step
       if (rc != DMTD_OK) {
         // device state may be ahead of the host's; resynchronise it to the host's unchanged view
         (void)hipStreamSynchronize(c->stream);
-        hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, (DevState*)(c->ws + c->o.state),
-                           c->sched.n_tok, c->sched.n_front);
+        hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state),
+                           c->sched.n_tok, c->sched.n_front, cf.max_batch);
         (void)hipStreamSynchronize(c->stream);
         return rc;
       }
@@ -1385,6 +1434,7 @@ int dmtd_decode_cycle_noalloc(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t 
   if (!n_emitted || (!out_tokens_dev && !cf.dry_run)) { c->err = "null output pointer"; return DMTD_EINVAL; }
   if (tau > kMaxTau) { c->err = "tau above the supported maximum (64)"; return DMTD_EINVAL; }
   if (forced_dev && n_forced < 1) { c->err = "forced inputs given with n_forced < 1"; return DMTD_EINVAL; }
+  if (c->diverged) { c->err = "the sequences are at different points of their cycles: use dmtd_decode_per_seq"; return DMTD_ESTATE; }
   std::vector<Step>& steps = c->plan_buf;       // capacity reserved at create: planning allocates nothing
   int err = 0;
   std::string why;
@@ -1458,6 +1508,183 @@ int dmtd_decode_cycle_noalloc(dmtd_ctx* c, int32_t tau, int32_t n_late, int32_t 
   }
   c->sched.commit(steps, n_late);
   *n_emitted = n;
+  return DMTD_OK;
+}
+
+int dmtd_decode_per_seq(dmtd_ctx* c, const int32_t* tau, int32_t n_late, int32_t n_steps, const int32_t* forced_inputs,
+                        int32_t n_forced, int32_t* out_tokens, int32_t out_stride, int32_t* n_emitted) {
+  if (!c) return DMTD_EINVAL;
+  const dmtd_config& cf = c->cfg;
+  if (n_emitted) *n_emitted = 0;
+  if (!out_tokens || !n_emitted || !tau) { c->err = "null pointer"; return DMTD_EINVAL; }
+  if (c->sched.n_tok == 0) { c->err = "decode before prefill"; return DMTD_ESTATE; }
+  if (n_steps < 1 || n_steps > kMaxTau) { c->err = "n_steps must be in [1, 64]"; return DMTD_EINVAL; }
+  if (n_late < 1 || n_late > cf.n_layers) { c->err = "n_late must be in [1, n_layers]"; return DMTD_EINVAL; }
+  if (c->sched.n_early != 0) { c->err = "per-sequence cycle lengths are not available in the ExDy variant"; return DMTD_ESTATE; }
+  if (forced_inputs && n_forced < 1) { c->err = "forced_inputs given with n_forced < 1"; return DMTD_EINVAL; }
+  if (out_stride < n_steps) { c->err = "out_stride smaller than the number of steps"; return DMTD_ECAPACITY; }
+  const int B = c->batch, n = n_steps;
+  for (int b = 0; b < B; ++b)
+    if (tau[b] < 1 || tau[b] > kMaxTau) { c->err = "every sequence's tau must be in [1, 64]"; return DMTD_EINVAL; }
+  if (c->sched.n_tok + n > cf.max_seq_len) { c->err = "sequence would exceed max_seq_len"; return DMTD_ECAPACITY; }
+  // plan on copies of the per-sequence state: rows[i][b] = 0 for a late-only step of sequence b, else its row count
+  std::vector<int> phase = c->diverged ? c->seq_phase : std::vector<int>(B, c->sched.phase);
+  std::vector<int> front = c->diverged ? c->seq_front : std::vector<int>(B, c->sched.n_front);
+  if (c->sched.n_late_in_use != 0 && c->sched.n_late_in_use != n_late)
+    for (int b = 0; b < B; ++b)
+      if (front[b] != c->sched.n_tok) { c->err = "n_late changed while tokens await refill"; return DMTD_ESTATE; }
+  std::vector<std::vector<int>> rows(n, std::vector<int>(B, 0));
+  int t = c->sched.n_tok;
+  for (int i = 0; i < n; ++i, ++t)
+    for (int b = 0; b < B; ++b) {
+      if (phase[b] >= tau[b]) {
+        rows[i][b] = t - front[b] + 1;
+        if (rows[i][b] > kMaxRows) { c->err = "more pending refill rows than the workspace holds"; return DMTD_ECAPACITY; }
+        front[b] = t + 1; phase[b] = 1;
+      } else {
+        phase[b] += 1;
+      }
+    }
+  const int f_stride = forced_inputs ? n_forced : 0;
+  const int nf = f_stride < n ? f_stride : n;
+  for (int b = 0; b < B && forced_inputs; ++b)
+    for (int i = 0; i < nf; ++i) {
+      const int32_t tk = forced_inputs[(size_t)b * f_stride + i];
+      if (tk < 0 || tk >= cf.vocab) { c->err = "forced token id outside the vocabulary"; return DMTD_EINVAL; }
+    }
+  if (!cf.dry_run) {
+    int* fdev = (int*)(c->ws + c->o.forced);
+    std::vector<int32_t> fhost((size_t)B * (nf > 0 ? nf : 1));
+    if (nf > 0) {
+      for (int b = 0; b < B; ++b)
+        for (int i = 0; i < nf; ++i) fhost[(size_t)b * nf + i] = forced_inputs[(size_t)b * f_stride + i];
+      HIP_TRY(c, hipMemcpyAsync(fdev, fhost.data(), (size_t)B * nf * 4, hipMemcpyHostToDevice, c->stream));
+    }
+    hipLaunchKernelGGL(begin_call_kernel, dim3(1), dim3(256), 0, c->stream, (DevState*)(c->ws + c->o.state),
+                       (int*)(c->ws + c->o.tokens), cf.max_seq_len, fdev, nf, nf, cf.vocab, B);
+    HIP_TRY(c, hipGetLastError());
+    std::vector<std::vector<char>> uploads;           // host images of new patterns: alive until the call's synchronisation
+    int rc = DMTD_OK;
+    for (int i = 0; i < n && rc == DMTD_OK; ++i) {
+      const int pos = c->sched.n_tok + i;
+      bool same = true;
+      for (int b = 1; b < B; ++b) same = same && rows[i][b] == rows[i][0];
+      if (same) {       // all sequences at the same point of their cycles: the ordinary step (and its graph)
+        rc = run_step(c, Step{rows[i][0] > 0, rows[i][0] > 0 ? rows[i][0] : 1, pos}, n_late);
+        continue;
+      }
+      choose_attention(c, pos + 1);
+      // the sequences that start a cycle, sorted by row count (one front pass per count)
+      std::vector<int> order;
+      for (int b = 0; b < B; ++b) if (rows[i][b] > 0) order.push_back(b);
+      std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return rows[i][x] < rows[i][y]; });
+      std::vector<std::pair<int, int>> groups;
+      for (int b : order) {
+        if (!groups.empty() && groups.back().first == rows[i][b]) groups.back().second += 1;
+        else groups.emplace_back(rows[i][b], 1);
+      }
+      // the pattern's device image: the list (ints) and the mask (bytes); cached patterns keep their slot for good (graphs
+      // refer to it), the last slot serves patterns beyond the table, without a graph
+      auto it = c->pattern_ids.find(rows[i]);
+      int slot;
+      const bool cached = it != c->pattern_ids.end() || (int)c->pattern_ids.size() < kMaxPatterns - 1;
+      if (it != c->pattern_ids.end()) slot = it->second;
+      else {
+        slot = cached ? (int)c->pattern_ids.size() : kMaxPatterns - 1;
+        uploads.emplace_back(kPatternStride(cf.max_batch), 0);
+        std::vector<char>& img = uploads.back();
+        for (size_t k = 0; k < order.size(); ++k) std::memcpy(img.data() + 4 * k, &order[k], 4);
+        for (int b = 0; b < B; ++b) img[(size_t)4 * cf.max_batch + b] = rows[i][b] > 0 ? 1 : 0;
+        hipError_t ce = hipMemcpyAsync(c->ws + c->o.patterns + (size_t)slot * kPatternStride(cf.max_batch), img.data(), img.size(),
+                                       hipMemcpyHostToDevice, c->stream);
+        if (ce != hipSuccess) { c->err = std::string("pattern upload: ") + hipGetErrorString(ce); rc = DMTD_EHIP; break; }
+        if (cached) c->pattern_ids.emplace(rows[i], slot);
+      }
+      const char* img_dev = c->ws + c->o.patterns + (size_t)slot * kPatternStride(cf.max_batch);
+      const int* list_dev = (const int*)img_dev;
+      const unsigned char* mask_dev = (const unsigned char*)img_dev + (size_t)4 * cf.max_batch;
+      if (!cf.use_graphs || !cached) {
+        hipError_t e = enqueue_step_mixed(c, groups, n_late, list_dev, mask_dev);
+        if (e != hipSuccess) { c->err = std::string("mixed step: ") + hipGetErrorString(e); rc = DMTD_EHIP; }
+        continue;
+      }
+      const std::vector<int> key = {slot, n_late, c->sampling ? 1 : 0, c->att_bucket, c->share_kv ? 1 : 0, B};
+      auto git = c->mixed_graphs.find(key);
+      if (git == c->mixed_graphs.end()) {
+        hipGraph_t graph = nullptr;
+        hipError_t e0 = hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal);
+        if (e0 != hipSuccess) { c->err = std::string("hipStreamBeginCapture: ") + hipGetErrorString(e0); rc = DMTD_EHIP; break; }
+        hipError_t e = enqueue_step_mixed(c, groups, n_late, list_dev, mask_dev);
+        hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
+        if (e != hipSuccess || e2 != hipSuccess) {
+          if (graph) (void)hipGraphDestroy(graph);
+          c->err = std::string("graph capture failed: ") + hipGetErrorString(e != hipSuccess ? e : e2);
+          rc = DMTD_EHIP; break;
+        }
+        hipGraphExec_t exec = nullptr;
+        hipError_t e3 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e3 != hipSuccess) { c->err = std::string("hipGraphInstantiate: ") + hipGetErrorString(e3); rc = DMTD_EHIP; break; }
+        git = c->mixed_graphs.emplace(key, exec).first;
+      }
+      hipError_t le = hipGraphLaunch(git->second, c->stream);
+      if (le != hipSuccess) { c->err = std::string("hipGraphLaunch: ") + hipGetErrorString(le); rc = DMTD_EHIP; }
+    }
+    if (rc != DMTD_OK) {
+      // back to the host's unchanged view: counters, and every sequence's front position
+      (void)hipStreamSynchronize(c->stream);
+      hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state), c->sched.n_tok, c->sched.n_front, cf.max_batch);
+      if (c->diverged) {
+        int* tmp = (int*)(c->ws + c->o.forced);
+        (void)hipMemcpyAsync(tmp, c->seq_front.data(), (size_t)B * 4, hipMemcpyHostToDevice, c->stream);
+        hipLaunchKernelGGL(set_fronts_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state), (const int*)tmp, B);
+      }
+      (void)hipStreamSynchronize(c->stream);
+      return rc;
+    }
+    std::vector<int32_t> em((size_t)n * B);
+    HIP_TRY(c, hipMemcpyAsync(em.data(), c->ws + c->o.emitted, em.size() * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (int b = 0; b < B; ++b)
+      for (int i = 0; i < n; ++i) out_tokens[(size_t)b * out_stride + i] = em[(size_t)i * B + b];
+  } else {
+    for (int b = 0; b < B; ++b)
+      for (int i = 0; i < n; ++i) out_tokens[(size_t)b * out_stride + i] = -1;
+  }
+  // commit: the counters and the trace follow sequence 0; the per-sequence state is kept while the sequences differ
+  const int F = cf.n_layers - n_late;
+  for (int i = 0; i < n; ++i) {
+    Sched& sc = c->sched;
+    sc.pass_no += 1;
+    if (rows[i][0] > 0) {
+      if (F > 0) sc.record(0, sc.n_tok - (rows[i][0] - 1), rows[i][0]);
+      sc.record(1, sc.n_tok, 1);
+      sc.gen_layer_visits += cf.n_layers;
+      sc.refill_layer_visits += (int64_t)(rows[i][0] - 1) * F;
+      sc.n_full_steps += 1;
+    } else {
+      sc.record(1, sc.n_tok, 1);
+      sc.gen_layer_visits += n_late;
+    }
+    sc.n_tok += 1;
+    sc.n_emitted += 1;
+  }
+  c->sched.n_late_in_use = n_late;
+  c->sched.n_front = front[0];
+  c->sched.phase = phase[0];
+  c->seq_phase = phase;
+  c->seq_front = front;
+  c->diverged = false;
+  for (int b = 1; b < B; ++b) c->diverged = c->diverged || phase[b] != phase[0] || front[b] != front[0];
+  *n_emitted = n;
+  return DMTD_OK;
+}
+
+int dmtd_get_seq_state(const dmtd_ctx* c, int32_t b, int32_t* n_front, int32_t* phase) {
+  if (!c) return DMTD_EINVAL;
+  if (b < 0 || b >= c->batch) return DMTD_EINVAL;
+  if (n_front) *n_front = c->diverged ? c->seq_front[b] : c->sched.n_front;
+  if (phase) *phase = c->diverged ? c->seq_phase[b] : c->sched.phase;
   return DMTD_OK;
 }
 
@@ -1620,7 +1847,7 @@ int dmtd_masked_forward(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32
                                                     hipMemcpyDeviceToHost, c->stream);
   // the caches served as scratch: back to the empty state on the device as on the host
   if (e == hipSuccess) {
-    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, dev_state(c), 0, 0);
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, dev_state(c), 0, 0, cf.max_batch);
     e = hipGetLastError();
   }
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
@@ -1648,7 +1875,7 @@ int dmtd_set_sampling(dmtd_ctx* c, float temperature, int32_t top_k, uint64_t se
 int dmtd_set_n_early(dmtd_ctx* c, int32_t n_early) {
   if (!c) return DMTD_EINVAL;
   if (n_early < 0 || n_early >= c->cfg.n_layers) { c->err = "n_early must be in [0, n_layers - 1]"; return DMTD_EINVAL; }
-  if (c->sched.n_tok != c->sched.n_front) { c->err = "n_early changed while tokens await refill"; return DMTD_ESTATE; }
+  if (c->sched.n_tok != c->sched.n_front || c->diverged) { c->err = "n_early changed while tokens await refill"; return DMTD_ESTATE; }
   if (c->sched.n_tok != 0 && c->cfg.full_pos_add_embed && n_early != c->sched.n_early) {
     c->err = "under the literal Eq. 4 reading n_early is fixed at prefill"; return DMTD_ESTATE;
   }
@@ -1660,13 +1887,16 @@ int dmtd_reset(dmtd_ctx* c) {
   if (!c) return DMTD_EINVAL;
   if (!c->cfg.dry_run) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, c->stream, (DevState*)(c->ws + c->o.state), 0, 0);
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, (DevState*)(c->ws + c->o.state), 0, 0, c->cfg.max_batch);
     HIP_TRY(c, hipGetLastError());
-    HIP_TRY(c, hipMemsetAsync(c->ws + c->o.state + kStateDeltaOff, 0, 8 * (size_t)c->cfg.max_batch, c->stream));
+    HIP_TRY(c, hipMemsetAsync(c->ws + c->o.state + kStateDeltaOff, 0, 12 * (size_t)c->cfg.max_batch, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
   }
   c->sched.reset();
   c->batch = 0;
+  c->diverged = false;
+  c->seq_phase.clear();
+  c->seq_front.clear();
   return DMTD_OK;
 }
 

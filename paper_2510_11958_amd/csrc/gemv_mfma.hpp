@@ -366,12 +366,13 @@ __device__ __forceinline__ void pack_row_for_norm(const float* __restrict__ h, c
 __global__ void __launch_bounds__(256) embed_pack_kernel(
     const bf16_t* __restrict__ table, const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset,
     int r, int d, float* __restrict__ h, const bf16_t* __restrict__ gain, bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo,
-    float* __restrict__ ssp) {
+    float* __restrict__ ssp, const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot */) {
   // One pass, 8 elements (16 bytes of the table row) per thread and turn, up to NCH turns' loads in flight at once;
   // the row's values stay in registers between the fp32 store, the packed store and the sum of squares.
   constexpr int NCH = 4;
   __shared__ float wsum[4];
-  const int row = blockIdx.x, b = row / r, i = row % r;
+  const int row = blockIdx.x, i = row % r;
+  const int b = fmap ? fmap[row / r] : row / r;
   const int pos = row_base(st, sel, offset, b) + i;
   const bf16_t* src = table + (size_t)tokens[(size_t)b * s_max + pos] * d;
   float* dst = h + (size_t)row * d;
@@ -421,11 +422,12 @@ __global__ void __launch_bounds__(256) take_last_pack_kernel(
     const float* __restrict__ src, float* dst, int r, int d, int add_embed, const bf16_t* __restrict__ table,
     const int* __restrict__ tokens, int s_max, const DevState* st, int sel, int offset, const bf16_t* __restrict__ gain,
     bf16_t* __restrict__ xb, bf16_t* __restrict__ xb_lo, float* __restrict__ ssp, const float* add_rows /* nullable; may be dst */,
-    const int* __restrict__ last_pos /* nullable: sequence b's row is the one at explicit position last_pos[b], if in this launch */) {
-  const int b = blockIdx.x;
+    const int* __restrict__ last_pos /* nullable: sequence b's row is the one at explicit position last_pos[b], if in this launch */,
+    const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot */) {
+  const int bl = blockIdx.x, b = fmap ? fmap[bl] : bl;         // source rows by launch sequence, everything else by slot
   const int i = last_pos ? last_pos[b] - offset : r - 1;
   if (i < 0 || i >= r) return;
-  const float* s = src + ((size_t)b * r + i) * d;
+  const float* s = src + ((size_t)bl * r + i) * d;
   float* o = dst + (size_t)b * d;
   const bf16_t* e = nullptr;
   if (add_embed) e = table + (size_t)tokens[(size_t)b * s_max + row_base(st, sel, offset, b) + i] * d;

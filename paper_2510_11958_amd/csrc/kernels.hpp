@@ -28,7 +28,12 @@ struct DevState {
   int step_idx;      // step number inside the current decode call
 };
 constexpr int kStateSampleOff = 64, kStateDeltaOff = 128;
-__device__ __forceinline__ const int* seq_delta(const DevState* st) { return (const int*)((const char*)st + kStateDeltaOff); }
+// Per sequence, from byte 128 on: its position offset against the counters, and the first of its positions that is not yet in
+// the front layers' caches (its own coordinates: n_front + delta while the sequences share one phase; its own value once their
+// cycle boundaries differ).  One 8-byte load gives both.  last_prompt_pos[max_batch] follows the max_batch pairs.
+struct SeqInfo { int delta; int front; };
+__device__ __forceinline__ SeqInfo* seq_info(DevState* st) { return (SeqInfo*)((char*)st + kStateDeltaOff); }
+__device__ __forceinline__ const SeqInfo* seq_info(const DevState* st) { return (const SeqInfo*)((const char*)st + kStateDeltaOff); }
 
 // Where a launch's rows sit: row i of sequence b is at position base + offset + i, with
 // base read from the device state plus the sequence's delta (or 0 for POS_EXPLICIT: explicit
@@ -37,7 +42,8 @@ enum PosSel : int { POS_NTOK = 0, POS_NFRONT = 1, POS_EXPLICIT = 2 };
 
 __device__ __forceinline__ int row_base(const DevState* st, int sel, int offset, int b) {
   if (sel == POS_EXPLICIT) return offset;
-  return (sel == POS_NTOK ? st->n_tok : st->n_front) + seq_delta(st)[b] + offset;
+  const SeqInfo si = seq_info(st)[b];
+  return (sel == POS_NTOK ? st->n_tok + si.delta : si.front) + offset;
 }
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
@@ -111,7 +117,7 @@ __global__ void begin_call_kernel(DevState* st, int* tokens, int s_max, const in
   const int base = st->n_tok;
   for (int i = threadIdx.x; i < batch * n_forced; i += blockDim.x) {
     const int b = i / n_forced, j = i % n_forced;
-    const int pos = base + seq_delta(st)[b] + j;
+    const int pos = base + seq_info(st)[b].delta + j;
     const int t = forced[(size_t)b * f_stride + j];
     if (pos < s_max) tokens[(size_t)b * s_max + pos] = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
   }
@@ -128,8 +134,14 @@ __global__ void zero_u64_kernel(unsigned long long* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0ull;
 }
 
-__global__ void set_state_kernel(DevState* st, int n_tok, int n_front) {
-  st->n_tok = n_tok; st->n_front = n_front; st->forced_until = 0; st->step_idx = 0;
+// Counters to (n_tok, n_front), every sequence's own front position to n_front + its delta (one phase for all).
+__global__ void set_state_kernel(DevState* st, int n_tok, int n_front, int max_batch) {
+  for (int b = threadIdx.x; b < max_batch; b += blockDim.x) seq_info(st)[b].front = n_front + seq_info(st)[b].delta;
+  if (threadIdx.x == 0) { st->n_tok = n_tok; st->n_front = n_front; st->forced_until = 0; st->step_idx = 0; }
+}
+// Every sequence's own front position from a list in the counters' coordinates (sequences at different points of their cycles).
+__global__ void set_fronts_kernel(DevState* st, const int* __restrict__ fronts, int batch) {
+  for (int b = threadIdx.x; b < batch; b += blockDim.x) seq_info(st)[b].front = fronts[b] + seq_info(st)[b].delta;
 }
 
 // Greedy selection keys: a logit and its vocabulary index packed into one 64-bit integer whose
@@ -147,7 +159,8 @@ __device__ __forceinline__ int argmax_key_index(unsigned long long key) { return
 // keys, and advance the state: one more token is in the late caches; a full step also closes
 // the refill gap.  With write_tokens == 0 only the keys are cleared (measurement launches).
 __global__ void __launch_bounds__(1024) finish_step_kernel(DevState* st, unsigned long long* amax, int n_cells /* <= 64 */, int amax_ld,
-                                                           int* tokens, int* emitted, int s_max, int batch, int full, int write_tokens) {
+                                                           int* tokens, int* emitted, int s_max, int batch, int full, int write_tokens,
+                                                           const unsigned char* __restrict__ full_mask /* nullable: the sequences for which this was a full step */) {
   const int pos = st->n_tok, step = st->step_idx, forced_until = st->forced_until;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   for (int b = wave; b < batch; b += n_waves) {      // one wave per sequence; lane = cell (keys are spread over n_cells cells)
@@ -164,14 +177,15 @@ __global__ void __launch_bounds__(1024) finish_step_kernel(DevState* st, unsigne
     if (lane == 0 && write_tokens) {
       const int tok = argmax_key_index(best);
       emitted[step * batch + b] = tok;
-      const int mine = pos + seq_delta(st)[b];       // this sequence's own position
+      const int mine = pos + seq_info(st)[b].delta;  // this sequence's own position
       if (mine + 1 < s_max && pos + 1 >= forced_until) tokens[(size_t)b * s_max + mine + 1] = tok;
+      if (full || (full_mask && full_mask[b])) seq_info(st)[b].front = mine + 1;     // its refill gap is closed
     }
   }
   __syncthreads();
   if (threadIdx.x == 0 && write_tokens) {
     st->n_tok = pos + 1;
-    if (full) st->n_front = pos + 1;
+    if (full || (full_mask && full_mask[0])) st->n_front = pos + 1;     // the shared counter follows sequence 0
     st->step_idx = step + 1;
   }
 }
@@ -180,8 +194,10 @@ __global__ void __launch_bounds__(1024) finish_step_kernel(DevState* st, unsigne
 // late layers read for in-cycle tokens).  Row b*r+i of the launch is sequence b, position base+i.
 template <typename WT>
 __global__ void embed_kernel(const WT* __restrict__ table, const int* __restrict__ tokens, int s_max,
-                             const DevState* st, int sel, int explicit_pos, int r, int d, float* __restrict__ h) {
-  const int row = blockIdx.x, b = row / r, i = row % r;
+                             const DevState* st, int sel, int explicit_pos, int r, int d, float* __restrict__ h,
+                             const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot */) {
+  const int row = blockIdx.x, i = row % r;
+  const int b = fmap ? fmap[row / r] : row / r;
   const int pos = row_base(st, sel, explicit_pos, b) + i;
   const int tok = tokens[(size_t)b * s_max + pos];
   const WT* src = table + (size_t)tok * d;
@@ -198,11 +214,11 @@ template <typename WT>
 __global__ void take_last_rows_kernel(const float* __restrict__ src, float* dst, int r, int d,
                                       int add_embed, const WT* __restrict__ table, const int* __restrict__ tokens,
                                       int s_max, const DevState* st, int sel, int explicit_pos, const float* add_rows,
-                                      const int* __restrict__ last_pos) {
-  const int b = blockIdx.x;
+                                      const int* __restrict__ last_pos, const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot */) {
+  const int bl = blockIdx.x, b = fmap ? fmap[bl] : bl;         // source rows by launch sequence, everything else by slot
   const int i = last_pos ? last_pos[b] - explicit_pos : r - 1;
   if (i < 0 || i >= r) return;
-  const float* s = src + ((size_t)b * r + i) * d;
+  const float* s = src + ((size_t)bl * r + i) * d;
   float* o = dst + (size_t)b * d;
   const WT* e = nullptr;
   if (add_embed) {
@@ -291,7 +307,7 @@ __global__ void __launch_bounds__(1024) sample_kernel(const float* __restrict__ 
     thr = prefix;
   }
   const unsigned long long seed = ((unsigned long long)cfg->seed_hi << 32) | cfg->seed_lo;
-  const unsigned long long stream = ((unsigned long long)(unsigned int)b << 32) | (unsigned int)(st->n_tok + seq_delta(st)[b]);
+  const unsigned long long stream = ((unsigned long long)(unsigned int)b << 32) | (unsigned int)(st->n_tok + seq_info(st)[b].delta);
   const unsigned long long base = splitmix_mix(splitmix_mix(seed + 0x9E3779B97F4A7C15ull) ^ (stream * 0xD6E8FEB86659FD93ull));
   unsigned long long key = 0ull;
   for (int v = tid; v < V; v += 1024) {

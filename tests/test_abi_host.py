@@ -299,3 +299,50 @@ def test_cycles_back_to_back_errors_leave_the_state_alone():
     assert lib.dmtd_decode(e._h, 3, 1, 5, None, 0, p, 4, C.byref(n)) == pkg.DMTD_ECAPACITY      # out_stride < n_steps
     assert e.state() == before
     assert e.decode(3, 1, 8).shape == (1, 8) and e.state()["n_tok"] == 12
+
+
+def test_per_sequence_cycle_lengths_schedule_like_one_oracle_per_sequence():
+    """dmtd_decode_per_seq in a dry run: every sequence's phase and refill point follow a standalone oracle machine run with
+    that sequence's cycle lengths; the single-phase calls are refused while the sequences differ and accepted once they
+    agree again; the counters and the trace follow sequence 0."""
+    import dmtd_inputs as di
+    from oracle import dmtd_oracle as O
+    sh = di.ModelShape(5, 32, 2, 1, 16, 48, 40, dtype="fp32")
+    cfg = O.OracleConfig(sh.n_layers, sh.hidden, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.intermediate, sh.vocab)
+    w = O.unpack_weights(di.make_weight_blob(sh, seed=1, std=0.2), cfg)
+    B, P, n_late = 3, 4, 2
+    eng = dry(n_layers=sh.n_layers, max_batch=B)          # only the schedule is compared: the engine's shape need not be the oracle's
+    eng.prefill(np.zeros((B, P), np.int32))
+    orcs = [O.DmtdOracle(cfg, w, 64) for _ in range(B)]
+    for o in orcs:
+        o.prefill([1, 2, 3, 4])
+    for taus, n in (([2, 3, 5], 7), ([2, 3, 5], 2), ([4, 4, 4], 6), ([1, 6, 2], 5)):
+        out = eng.decode_per_seq(taus, n_late, n)
+        assert out.shape == (B, n)
+        for b, o in enumerate(orcs):
+            done = 0
+            while done < n:
+                done += len(o.decode_cycle(taus[b], n_late, max_new=n - done))
+            s = eng.seq_state(b)
+            assert (eng.state()["n_tok"], s["n_front"], s["phase"]) == (o.n_tok, o.n_front, o.phase), (taus, b)
+    s0, o0 = eng.state(), orcs[0]
+    assert (s0["gen_layer_visits"], s0["refill_layer_visits"], s0["n_emitted"]) == (o0.gen_layer_visits, o0.refill_layer_visits, o0.n_emitted)
+    assert eng.trace() == [(p + 1, g, pos) for p, t in enumerate(o0.trace) for g, pos in t]
+    with pytest.raises(pkg.DmtdError) as e:
+        eng.decode_cycle(3, n_late)
+    assert e.value.code == pkg.DMTD_ESTATE
+    # argument errors leave everything alone
+    before = [eng.seq_state(b) for b in range(B)]
+    for bad_taus, n, code in (([2, 0, 3], 3, pkg.DMTD_EINVAL), ([2, 3, 65], 3, pkg.DMTD_EINVAL), ([2, 3, 4], 0, pkg.DMTD_EINVAL),
+                              ([2, 3, 4], 65, pkg.DMTD_EINVAL), ([30, 30, 30], 40, pkg.DMTD_ECAPACITY)):
+        with pytest.raises(pkg.DmtdError) as e:
+            eng.decode_per_seq(bad_taus, n_late, n)
+        assert e.value.code == code, bad_taus
+    assert [eng.seq_state(b) for b in range(B)] == before
+    # a cycle longer than the rows a pass can carry (16) cannot be refilled in one pass
+    eng.reset()
+    eng.prefill(np.zeros((B, P), np.int32))
+    eng.decode_per_seq([20, 2, 2], n_late, 19)
+    with pytest.raises(pkg.DmtdError) as e:
+        eng.decode_per_seq([20, 2, 2], n_late, 1)
+    assert e.value.code == pkg.DMTD_ECAPACITY
