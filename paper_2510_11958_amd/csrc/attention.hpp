@@ -178,13 +178,44 @@ __device__ __forceinline__ void attn_prepare_rows(
   }
 }
 
+// QK-RMSNorm + RoPE + KV append as a launch of its own, for passes that carry more rows per sequence than an attention
+// block keeps in LDS (prefill, the whole-sequence forward): per-head RMSNorm and rotation of the rows' keys, and their
+// values, rounded to the cache's type and stored; the attention launch that follows then finds every key in the cache
+// (do_append = 2).  One wave per (row, KV head).
+template <typename CT, int HD>
+__global__ void __launch_bounds__(64) kv_append_kernel(
+    const float* __restrict__ qkv, int ldq, const void* __restrict__ k_gain, const float2* __restrict__ rope_tab,
+    CT* __restrict__ kc, CT* __restrict__ vc, int nh, int nkv, int s_max, float eps, const DevState* st, int sel, int offset, int r_total) {
+  constexpr int half = HD / 2;
+  const int row_g = blockIdx.x, g = blockIdx.y, lane = threadIdx.x;
+  const int b = row_g / r_total, i = row_g % r_total;
+  const int key = row_base(st, sel, offset, b) + i;
+  const float* ksrc = qkv + (size_t)row_g * ldq + (size_t)(nh + g) * HD;
+  const float* vsrc = qkv + (size_t)row_g * ldq + (size_t)(nh + nkv + g) * HD;
+  const bool act = lane < half;
+  float x0 = act ? ksrc[lane] : 0.f, x1 = act ? ksrc[lane + half] : 0.f;
+  const float rs = rsqrtf(wave_sum(x0 * x0 + x1 * x1) / (float)HD + eps);
+  CT* kd = kc + (((size_t)b * nkv + g) * s_max + key) * HD;
+  CT* vd = vc + (((size_t)b * nkv + g) * s_max + key) * HD;
+  if (act) {
+    const CT* gn = (const CT*)k_gain;
+    x0 *= rs * Elem<CT>::to_f32(gn[lane]);
+    x1 *= rs * Elem<CT>::to_f32(gn[lane + half]);
+    const float2 cs = rope_tab[(size_t)key * half + lane];
+    kd[lane] = Elem<CT>::from_f32(x0 * cs.x - x1 * cs.y);
+    kd[lane + half] = Elem<CT>::from_f32(x1 * cs.x + x0 * cs.y);
+  }
+  for (int k = lane; k < HD; k += 64) vd[k] = Elem<CT>::from_f32(vsrc[k]);
+}
+
 template <typename CT, int HD, int QVT>
 __global__ void __launch_bounds__(256) attn_split_kernel(
     const float* __restrict__ qkv, int ldq, const void* __restrict__ q_gain, const void* __restrict__ k_gain,
     const float2* __restrict__ rope_tab /* [s_max][HD / 2] (cos, sin) of position * theta^(-2i/HD) */, CT* __restrict__ kc, CT* __restrict__ vc,
     float* __restrict__ part_o, float* __restrict__ part_ml, int nh, int nkv, int s_max, float eps,
     int kps /* keys per range, a multiple of the block iteration */, int n_splits, int qv_stride,
-    const DevState* st, int sel, int offset, int r_total, int do_append /* 0: leave the cache untouched (measurement) */,
+    const DevState* st, int sel, int offset, int r_total,
+    int do_append /* 1: the launch appends its rows' keys and values; 0: it scores them from its inputs and leaves the cache untouched (measurement); 2: they are in the cache already */,
     const int* __restrict__ fmap /* nullable: launch sequence -> sequence slot (cache rows, positions) */) {
   typedef typename Elem<CT>::Raw Raw;
   constexpr int LPK = HD / 8;          // lanes per key (16 or 8)
@@ -238,8 +269,8 @@ __global__ void __launch_bounds__(256) attn_split_kernel(
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
   const int key_end = min(ctx, key_begin + kps);
   const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
-  const bool holds_new = key_end > pos_first;                   // a new position falls into this range
-  const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
+  const bool holds_new = do_append != 2 && key_end > pos_first; // a new position, not yet in the cache, falls into this range
+  const bool writer = do_append == 1 && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
   const float scale = rsqrtf((float)HD);
 
   attn_prepare_rows<CT, HD>(qkv, ldq, q_gain, k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total, rg * rpb, QV, n_new, holds_new,

@@ -283,8 +283,8 @@ __global__ void __launch_bounds__(64 * NW) attn_split_mfma_kernel(
   if (key_begin >= ctx) return;                                 // whole range beyond the context (block-uniform)
   const int key_end = min(ctx, key_begin + kps);
   const int n_new = rg * rpb + r;                               // new rows whose keys this block's rows can see
-  const bool holds_new = key_end > pos_first;
-  const bool writer = do_append && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
+  const bool holds_new = do_append != 2 && key_end > pos_first;      // do_append = 2: the rows' keys are in the cache already
+  const bool writer = do_append == 1 && (rg + 1) * rpb >= r_total;   // the last row group's blocks append to the cache
 
   attn_prepare_rows_mfma<HD>(qs, (const bf16_t*)q_gain, (const bf16_t*)k_gain, rope_tab, kc, vc, b, g, nh, nkv, s_max, eps, r_total,
                              rg * rpb, QV, n_new, holds_new, writer, pos_first, key_begin, key_end, qhi_s, qlo_s, knew_s, vnew_s, tid, NT / 16, qpre);

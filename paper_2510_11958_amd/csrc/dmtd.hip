@@ -31,7 +31,11 @@ namespace {
 constexpr int kMaxTau = 64;          // steps per decode call (size of the emitted-token buffer)
 constexpr int kGemvRows = 4;         // activation rows per FMA weight-streaming pass
 constexpr int kMaxRows = 16;         // rows per sequence one pass through the layers may carry
-constexpr int kPrefillChunk = 16;    // prompt positions per prefill pass (per sequence)
+constexpr int kPassRows = 128;       // activation rows (all sequences together) a prefill or whole-sequence pass carries: one weight pass of the tiled kernel
+// Row capacity of the activation buffers, and positions per sequence of a prefill pass: passes of kPassRows rows in all,
+// at least kMaxRows per sequence (large batches: more passes of the tiled kernel per weight stream are not needed, B * 16 >= 128)
+inline int row_capacity(int max_batch) { return max_batch * kMaxRows > kPassRows ? max_batch * kMaxRows : kPassRows; }
+inline int pass_positions(int batch) { const int r = kPassRows / batch; return r > kMaxRows ? r : kMaxRows; }
 constexpr int kMaxPatterns = 64;     // distinct step patterns (which sequences start a cycle, with how many rows) a context keeps on the device
 constexpr size_t kPatternStride(size_t max_batch) { return (max_batch * 5 + 255) / 256 * 256; }   // int list [max_batch] + byte mask [max_batch]
 constexpr int kMfmaRows = 16;        // activation rows per pass of the one-tile-per-block MFMA kernel
@@ -219,7 +223,7 @@ Ws layout(const dmtd_config& c) {
   const size_t e = c.dtype == DMTD_DTYPE_F32 ? 4 : 2;
   const size_t B = c.max_batch, S = c.max_seq_len, d = c.hidden, hd = c.head_dim;
   const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * hd, qd = (size_t)c.n_q_heads * hd;
-  const size_t rows = B * kMaxRows;
+  const size_t rows = row_capacity(c.max_batch);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t kv_one = B * c.n_kv_heads * S * hd * e;       // K (or V) of one layer
@@ -232,9 +236,11 @@ Ws layout(const dmtd_config& c) {
   w.attn = take(rows * qd * 4);                       // fp32 path: fp32 rows; packed path: bf16 rows
   w.mlp = take(rows * (size_t)c.intermediate * 4);    // likewise
   w.logits = take(B * (size_t)c.vocab * 4);
-  const size_t qv_stride = (size_t)kMaxRows * (c.n_q_heads / c.n_kv_heads);
-  w.part_o = take(B * c.n_kv_heads * ATT_MAX_SPLITS * qv_stride * hd * 4);
-  w.part_ml = take(B * c.n_kv_heads * ATT_MAX_SPLITS * qv_stride * 2 * 4);
+  // partial results of the attention key ranges: laid out per sequence for kMaxRows rows in decode steps and for a pass's
+  // positions in prefill; sequences x rows per sequence never exceeds the row capacity
+  const size_t qv_rows = rows * (c.n_q_heads / c.n_kv_heads);
+  w.part_o = take(c.n_kv_heads * ATT_MAX_SPLITS * qv_rows * hd * 4);
+  w.part_ml = take(c.n_kv_heads * ATT_MAX_SPLITS * qv_rows * 2 * 4);
   w.amax = take((size_t)AMAX_CELLS * B * 8);
   w.tokens = take(B * S * 4);
   w.emitted = take((size_t)kMaxTau * B * 4);
@@ -594,7 +600,7 @@ template <typename CT, typename OT>
 hipError_t launch_attention(dmtd_ctx* c, int l, const float* qkv, OT* attn, OT* attn_lo, int sel, int offset, int r, int append = 1) {
   const dmtd_config& cf = c->cfg;
   const int gq = cf.n_q_heads / cf.n_kv_heads;
-  if (r > kMaxRows) return hipErrorInvalidValue;
+  if (r > kMaxRows && append != 2) return hipErrorInvalidValue;    // more rows than an attention block keeps in LDS: their keys must be in the cache
   if constexpr (std::is_same<CT, bf16_t>::value) {
     if (cf.head_dim == 128) return launch_attention_mfma_t<OT, 128>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
     return launch_attention_mfma_t<OT, 64>(c, l, qkv, attn, attn_lo, sel, offset, r, append);
@@ -664,6 +670,24 @@ hipError_t take_last_rows(dmtd_ctx* c, const Rows& src, Rows& dst, int r, int ad
   return hipGetLastError();
 }
 
+// a3 as a launch of its own, for passes with more rows per sequence than an attention block keeps in LDS (prefill, the
+// whole-sequence forward): the rows' keys (QK-RMSNorm + RoPE) and values go to the cache before the attention launch
+template <typename CT>
+hipError_t launch_kv_append(dmtd_ctx* c, int l, const float* qkv, int sel, int offset, int r) {
+  const dmtd_config& cf = c->cfg;
+  const int nqkv = (cf.n_q_heads + 2 * cf.n_kv_heads) * cf.head_dim;
+  CT* kc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride);
+  CT* vc = (CT*)(c->ws + c->o.kv + (size_t)l * c->o.kv_layer_stride + c->o.kv_v_off);
+  const dim3 grid(c->batch * r, cf.n_kv_heads);
+  if (cf.head_dim == 128)
+    hipLaunchKernelGGL((kv_append_kernel<CT, 128>), grid, dim3(64), 0, c->stream, qkv, nqkv, c->layers[l].k_norm, (const float2*)(c->ws + c->o.rope_tab),
+                       kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, cf.rms_eps, (const DevState*)dev_state(c), sel, offset, r);
+  else
+    hipLaunchKernelGGL((kv_append_kernel<CT, 64>), grid, dim3(64), 0, c->stream, qkv, nqkv, c->layers[l].k_norm, (const float2*)(c->ws + c->o.rope_tab),
+                       kc, vc, cf.n_q_heads, cf.n_kv_heads, cf.max_seq_len, cf.rms_eps, (const DevState*)dev_state(c), sel, offset, r);
+  return hipGetLastError();
+}
+
 // a2..a7: one transformer block over r rows per sequence at positions base + offset + i
 hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   const dmtd_config& cf = c->cfg;
@@ -674,7 +698,7 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   hipError_t e;
   if (c->packed) {
     const LayerSw& s = c->sw[l];
-    const size_t rows_cap = (size_t)cf.max_batch * kMaxRows;
+    const size_t rows_cap = row_capacity(cf.max_batch);
     bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);      // attention output, high parts; low parts behind them
     bf16_t* ab_lo = ab + rows_cap * qd;
     bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);       // SwiGLU output, likewise
@@ -684,12 +708,14 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
     // a2: RMSNorm + fused QKV projection
     a.W = s.qkv; a.xb = R.xb; a.xb_lo = R.xb_lo; a.ldxb = d; a.N = nqkv; a.K = d; a.ssp = R.ssp; a.n_parts = R.n_parts; a.ssp_ld = c->ssp_ld;
     a.eps = cf.rms_eps; a.y = qkv; a.ldy = nqkv;
-    c->fold_qkv = true;
+    const bool wide = r > kMaxRows;      // more rows per sequence than an attention block keeps in LDS: the append is a launch of its own
+    c->fold_qkv = !wide;
     e = launch_qkv(c, a, rows);
     c->fold_qkv = false;
     if (e != hipSuccess) { c->qkv_pending = QkvSrc{}; return e; }
     // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge (output packed for the O projection)
-    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, ab_lo, sel, offset, r)) != hipSuccess) return e;
+    if (wide && (e = launch_kv_append<bf16_t>(c, l, qkv, sel, offset, r)) != hipSuccess) return e;
+    if ((e = launch_attention<bf16_t, bf16_t>(c, l, qkv, ab, ab_lo, sel, offset, r, wide ? 2 : 1)) != hipSuccess) return e;
     // a5: O projection + residual; emits the MLP norm's input
     a = MfmaArgs{};
     a.W = s.o; a.xb = ab; a.xb_lo = ab_lo; a.ldxb = qd; a.N = d; a.K = qd; a.y = R.h; a.ldy = d; a.yb = R.xb; a.yb_lo = R.xb_lo; a.ldyb = d;
@@ -717,7 +743,8 @@ hipError_t run_layer(dmtd_ctx* c, int l, Rows& R, int r, int sel, int offset) {
   a.W = w.q; a.gain = w.attn_norm; a.x = R.h; a.ldx = d; a.y = qkv; a.ldy = nqkv; a.N = nqkv; a.K = d;
   if ((e = gemv_rows<float, EPI_STORE, true>(c, a, rows)) != hipSuccess) return e;
   // a3 + a4: QK-RMSNorm + RoPE + KV append + split-K attention, then the merge
-  if ((e = launch_attention<float, float>(c, l, qkv, attn, (float*)nullptr, sel, offset, r)) != hipSuccess) return e;
+  if (r > kMaxRows && (e = launch_kv_append<float>(c, l, qkv, sel, offset, r)) != hipSuccess) return e;
+  if ((e = launch_attention<float, float>(c, l, qkv, attn, (float*)nullptr, sel, offset, r, r > kMaxRows ? 2 : 1)) != hipSuccess) return e;
   // a5: O projection + residual
   a = GemvArgs{};
   a.W = w.o; a.x = attn; a.ldx = qd; a.y = R.h; a.ldy = d; a.N = d; a.K = qd;
@@ -769,7 +796,7 @@ hipError_t run_head(dmtd_ctx* c, const Rows& R, int full, int write_tokens, int 
 
 Rows front_rows(dmtd_ctx* c) {
   bf16_t* xb = (bf16_t*)(c->ws + c->o.xb);
-  return Rows{(float*)(c->ws + c->o.h), xb, xb + (size_t)c->cfg.max_batch * kMaxRows * c->cfg.hidden, (float*)(c->ws + c->o.ssp), 1};
+  return Rows{(float*)(c->ws + c->o.h), xb, xb + (size_t)row_capacity(c->cfg.max_batch) * c->cfg.hidden, (float*)(c->ws + c->o.ssp), 1};
 }
 Rows late_rows(dmtd_ctx* c) {
   bf16_t* xb = (bf16_t*)(c->ws + c->o.xb_late);
@@ -993,6 +1020,11 @@ int run_steps_grouped(dmtd_ctx* c, const std::vector<Step>& steps, int tau, int 
   return DMTD_OK;
 }
 
+struct PartRowsGuard {     // restores the partials' row layout on every way out of a prefill-type pass
+  dmtd_ctx* c; int saved;
+  ~PartRowsGuard() { c->part_rows = saved; }
+};
+
 // Prefill (Sec. 2.2): all prompt positions through all layers, in chunks of rows
 hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
   const dmtd_config& cf = c->cfg;
@@ -1001,8 +1033,11 @@ hipError_t enqueue_prefill(dmtd_ctx* c, int P, int n_late, bool ragged) {
   hipError_t e;
   hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, dev_state(c), P - 1, P - 1, cf.max_batch);
   int r_last = 0, p_last = 0;
-  for (int p0 = 0; p0 < P; p0 += kPrefillChunk) {
-    const int r = P - p0 < kPrefillChunk ? P - p0 : kPrefillChunk;
+  const int chunk = pass_positions(c->batch);
+  PartRowsGuard guard{c, c->part_rows};
+  c->part_rows = chunk;                 // the attention partials are laid out for a pass's rows per sequence
+  for (int p0 = 0; p0 < P; p0 += chunk) {
+    const int r = P - p0 < chunk ? P - p0 : chunk;
     choose_attention(c, p0 + r);
     if ((e = embed_rows(c, front, POS_EXPLICIT, p0, r, 0)) != hipSuccess) return e;
     const int E = c->sched.n_early;
@@ -1060,7 +1095,7 @@ hipError_t enqueue_masked_chunk(dmtd_ctx* c, int p0, int r, int n, int n_late) {
   for (int l = F; l < cf.n_layers; ++l)
     if ((e = run_layer(c, l, R, r, POS_EXPLICIT, p0)) != hipSuccess) return e;
   float* logits = (float*)(c->ws + c->o.logits_rows);
-  if ((e = head_logits(c, R, rows, logits, (unsigned long long*)(c->ws + c->o.amax_rows), cf.max_batch * kMaxRows)) != hipSuccess) return e;
+  if ((e = head_logits(c, R, rows, logits, (unsigned long long*)(c->ws + c->o.amax_rows), row_capacity(cf.max_batch))) != hipSuccess) return e;
   hipLaunchKernelGGL(nll_rows_kernel, dim3(rows), dim3(1024), 0, c->stream, (const float*)logits, cf.vocab, (const int*)dev_tokens(c), cf.max_seq_len,
                      p0, r, n, (float*)(c->ws + c->o.nll), (int*)(c->ws + c->o.best));
   return hipGetLastError();
@@ -1081,7 +1116,7 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
     const int r = rows <= last + 1 ? rows : 1;
     // the cache append is switched off: the launch scores the rows' new keys from the scratch q/k/v, writes nothing
     choose_attention(c, last + 1);
-    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (bf16_t*)(c->ws + c->o.attn) + (size_t)cf.max_batch * kMaxRows * cf.n_q_heads * cf.head_dim, (int)POS_EXPLICIT, last - r + 1, r, 0);
+    if (c->packed) return launch_attention<bf16_t, bf16_t>(c, l, qkv, (bf16_t*)(c->ws + c->o.attn), (bf16_t*)(c->ws + c->o.attn) + (size_t)row_capacity(cf.max_batch) * cf.n_q_heads * cf.head_dim, (int)POS_EXPLICIT, last - r + 1, r, 0);
     return launch_attention<float, float>(c, l, qkv, (float*)(c->ws + c->o.attn), (float*)nullptr, (int)POS_EXPLICIT, last - r + 1, r, 0);
   }
   if (kind == DMTD_K_LMHEAD) {
@@ -1090,7 +1125,7 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
   }
   if (c->packed) {
     const LayerSw& s = c->sw[l];
-    const size_t rows_cap = (size_t)cf.max_batch * kMaxRows;
+    const size_t rows_cap = row_capacity(cf.max_batch);
     bf16_t* ab = (bf16_t*)(c->ws + c->o.attn);
     bf16_t* ab_lo = ab + rows_cap * qd;
     bf16_t* ub = (bf16_t*)(c->ws + c->o.mlp);
@@ -1182,7 +1217,7 @@ int dmtd_create(const dmtd_config* cfg, const void* weights_dev, size_t weights_
   c->sched.n_layers = cfg->n_layers;
   c->sched.max_seq_len = cfg->max_seq_len;
   c->packed = cfg->dtype == DMTD_DTYPE_BF16;
-  c->ssp_ld = cfg->max_batch * kMaxRows;
+  c->ssp_ld = row_capacity(cfg->max_batch);
   if (const char* ev = std::getenv("DMTD_TEST_FAIL_STEP")) c->test_fail_step = std::atoi(ev);
   c->plan_buf.reserve(kMaxTau + 1);
   c->sched.trace.reserve((size_t)12 * cfg->max_seq_len + 64);        // at most 3 records of 4 per step: later steps never reallocate
@@ -1760,7 +1795,7 @@ int dmtd_read_kv(dmtd_ctx* c, int32_t layer, int32_t b, int32_t n_pos, float* ou
 int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, float* avg_us) {
   if (!c) return DMTD_EINVAL;
   // attention: rows per sequence (at most 16); projections: total activation rows (at most max_batch * 16, the row buffers' capacity)
-  const int rows_max = kind == DMTD_K_ATTN ? kMaxRows : c->cfg.max_batch * kMaxRows;
+  const int rows_max = kind == DMTD_K_ATTN ? kMaxRows : row_capacity(c->cfg.max_batch);
   if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > rows_max || reps < 1) {
     c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
   }
@@ -1823,8 +1858,11 @@ int dmtd_masked_forward(dmtd_ctx* c, const int32_t* tokens, int32_t batch, int32
   hipError_t e = hipMemcpy2DAsync(c->ws + c->o.tokens, (size_t)cf.max_seq_len * 4, tokens, (size_t)n * 4, (size_t)n * 4, batch,
                                   hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->ws + c->o.mask, m32.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
-  for (int p0 = 0; p0 < n && e == hipSuccess; p0 += kPrefillChunk) {
-    const int r = n - p0 < kPrefillChunk ? n - p0 : kPrefillChunk;
+  const int chunk = pass_positions(batch);
+  PartRowsGuard guard{c, c->part_rows};
+  c->part_rows = chunk;
+  for (int p0 = 0; p0 < n && e == hipSuccess; p0 += chunk) {
+    const int r = n - p0 < chunk ? n - p0 : chunk;
     e = enqueue_masked_chunk(c, p0, r, n, n_late);
     if (logits && e == hipSuccess) {
       // the chunk's rows of sequence b follow each other: one copy per sequence, before the next chunk reuses the buffer
