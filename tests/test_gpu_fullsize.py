@@ -252,16 +252,43 @@ def test_batch_rows_are_independent_and_identical_prompts_agree(model_4b):
 
 
 def test_long_context_attention_one_layer():
-    """C5's context length (16384 + decode) on a one-layer model with C5's head geometry, whole path against
-    the float64 oracle: exercises split-K attention, the merge and cache indexing at 16k positions."""
+    """C5's batch and context length (8 sequences x 16384-token prompts + decode) on a one-layer model with C5's head
+    geometry, whole path through the C ABI: split-K attention over 16k keys per sequence, the merge and cache indexing,
+    steps with one row and with three rows per sequence (tau = 3).  Sequences 0 and 7 against standalone float64 oracle
+    runs (batch rows are independent); every sequence's token must be the argmax of its logits."""
     sh = di.ModelShape(1, 512, 32, 8, 128, 1024, 2048, dtype="bf16")
     blob = di.make_weight_blob(sh, seed=2, std=0.05, gain_sigma=0.2)
-    B, P = 2, 16384
+    B, P, tau, n_late = 8, 16384, 3, 1
     prompts = di.make_prompts(sh.vocab, B, P, seed=9)
     toks = forced_string(sh.vocab, B, prompts, P + 16)
-    p = Pair(sh, blob, P + 16, batch=B)
-    p.prefill(prompts)
-    for _ in range(5):
-        p.step_forced(3, 1, toks)
-    assert p.worst < TOL_BF16, p.worst
-    print(f"long context: worst {p.worst:.2e}, tokens checked {p.token_checks}")
+    eng = pkg.Engine(engine_config(sh, P + 16, B), blob)
+    ocfg = oracle_config(sh)
+    w = O.unpack_weights(blob, ocfg, np.float64)
+    picks = (0, B - 1)
+    orcs = {b: O.DmtdOracle(ocfg, w, P + 16, np.float64) for b in picks}
+    first = eng.prefill(prompts)
+    worst, checked = 0.0, 0
+    for b, o in orcs.items():
+        o.prefill(prompts[b])
+        worst, ref = _check_against_oracle(eng, o, b, worst)
+        if top2_margin(ref) > MARGIN:
+            assert int(first[b]) == int(np.argmax(ref))
+    for _ in range(6):
+        nt = eng.state()["n_tok"]
+        f = np.stack([toks[b][nt:nt + 1] for b in range(B)])
+        out = eng.decode_cycle(tau, n_late, max_new=1, forced=f)
+        assert np.array_equal(out[:, 0], np.argmax(eng.logits(), axis=1))
+        for b, o in orcs.items():
+            o.decode_cycle(tau, n_late, max_new=1, forced=f[b].tolist())
+            worst, ref = _check_against_oracle(eng, o, b, worst)
+            if top2_margin(ref) > MARGIN:
+                assert int(out[b, 0]) == int(np.argmax(ref))
+                checked += 1
+    assert worst < TOL_BF16, worst
+    n = eng.state()["n_tok"]
+    for b, o in orcs.items():
+        kv = eng.read_kv(0, b, n)
+        for which, ref in ((0, o.K[0]), (1, o.V[0])):
+            r = np.transpose(ref[:n], (1, 0, 2))
+            assert np.abs(kv[which][:, :n] - r).max() / np.abs(r).max() < 1e-2
+    print(f"long context (B={B}, P={P}): worst {worst:.2e}, tokens checked {checked}")
