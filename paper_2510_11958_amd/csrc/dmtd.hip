@@ -387,6 +387,20 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
   // up to most of a CU's LDS when the launch has no more blocks than the chip has CUs anyway.  Rows that do not
   // fit, and more than 16 rows (batched steps), go through the LDS-tiled kernel in passes of up to kGemmRows rows.
   const bool fits = a.ldxb == a.K && mfma_rows_fit(c, rows, a.N, a.K, NORM ? a.n_parts : 0);
+  // one launch of the tiled kernel; with 64 and more rows its ring of activation slices is dynamic LDS beyond the default limit
+#define DMTD_LAUNCH_GEMM(CG_, SPLIT_, GRID_)                                                                                   \
+  do {                                                                                                                         \
+    auto kern = gemm_mfma_kernel<EPI, NORM, CG_, SPLIT_>;                                                                      \
+    constexpr size_t dyn = gemm_dyn_lds(CG_);                                                                                  \
+    static bool big_lds = false;                                                                                               \
+    if (dyn > 0 && !big_lds) {                                                                                                 \
+      hipError_t ae = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);            \
+      if (ae != hipSuccess) return ae;                                                                                         \
+      big_lds = true;                                                                                                          \
+    }                                                                                                                          \
+    hipLaunchKernelGGL(kern, GRID_, dim3(64 * gemm_waves(CG_, EPI)), dyn, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, \
+                       g.ldxb, g.ksplit, g);                                                                                   \
+  } while (0)
   if (!fits) {
     const int n_tiles = (a.N + 15) / 16;
     for (int m0 = 0; m0 < rows; m0 += kGemmRows) {
@@ -425,10 +439,10 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
           g.ldp = (EPI == EPI_SWIGLU ? 2 : 1) * a.N;
           g.part = c->gemm_part;
           const dim3 sgrid(ggrid.x, ksplit);
-          if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, true>), sgrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-          else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, true>), sgrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-          else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, true>), sgrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-          else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, true>), sgrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+          if (cg == 1) DMTD_LAUNCH_GEMM(1, true, sgrid);
+          else if (cg == 2) DMTD_LAUNCH_GEMM(2, true, sgrid);
+          else if (cg == 4) DMTD_LAUNCH_GEMM(4, true, sgrid);
+          else DMTD_LAUNCH_GEMM(8, true, sgrid);
           if (EPI == EPI_STORE && NORM && c->fold_qkv && rows <= kGemmRows && ksplit <= ATT_KSMAX && c->batch > 0 &&
               attention_single_range(c, rows / c->batch)) {
             // the attention launch that follows sums the splits and applies the norm scale while it prepares its rows; only in
@@ -441,10 +455,10 @@ hipError_t launch_mfma(dmtd_ctx* c, MfmaArgs a, int rows) {
           }
         }
       } else {
-        if (cg == 1) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 1, false>), ggrid, dim3(64 * gemm_waves(1, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-        else if (cg == 2) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 2, false>), ggrid, dim3(64 * gemm_waves(2, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-        else if (cg == 4) hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 4, false>), ggrid, dim3(64 * gemm_waves(4, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
-        else hipLaunchKernelGGL((gemm_mfma_kernel<EPI, NORM, 8, false>), ggrid, dim3(64 * gemm_waves(8, EPI)), 0, c->stream, g.W, g.W2, g.xb, g.xb_lo, g.M, g.N, g.K, g.ldxb, g.ksplit, g);
+        if (cg == 1) DMTD_LAUNCH_GEMM(1, false, ggrid);
+        else if (cg == 2) DMTD_LAUNCH_GEMM(2, false, ggrid);
+        else if (cg == 4) DMTD_LAUNCH_GEMM(4, false, ggrid);
+        else DMTD_LAUNCH_GEMM(8, false, ggrid);
       }
     }
     return hipGetLastError();

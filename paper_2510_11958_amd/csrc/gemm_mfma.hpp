@@ -10,7 +10,8 @@
 //     (2 with 64 and more rows);
 //   * activations: the k-step's slice of all rows, both bf16 planes (see gemv_mfma.hpp), fetched
 //     by all threads as far ahead into registers, written to one of two LDS buffers and shared
-//     by the block's tiles, every B fragment feeding the matrix cores twice (one per tile of a wave).
+//     by the block's tiles, every B fragment feeding the matrix cores twice (one per tile of a wave);
+//     with 128 rows the slices go from memory straight into a ring of LDS buffers instead (see below).
 // One block barrier per k-step.  A wave owns its tiles over the block's whole k-range, so nothing is
 // reduced across waves.  The loop is laid out so that every wait counts exactly the loads that may stay
 // in flight: the first PF steps are issued without a bounds check, the main loop covers only steps whose
@@ -53,6 +54,23 @@ __device__ __forceinline__ void static_for(F&& f) {
 // With 128 rows the accumulators leave registers for 8 waves only in the SwiGLU kernel (the others would spill).
 constexpr int gemm_waves(int cg, int epi) { return (cg >= 2 && epi != EPI_RESID && (cg <= 4 || epi == EPI_SWIGLU)) ? 8 : 4; }
 
+// With 64 and more rows (DMA) the activation slices do not pass through registers: every wave sends its share of a
+// k-step's slice from memory straight into LDS (global_load ... lds: lane l of an instruction lands 16 bytes at the
+// instruction's LDS base + 16 l), into a ring of PF + 1 slices, so the accumulators and PF k-steps of weights are all the
+// registers hold and a slice is requested PF steps (several microseconds) before it is used.  LDS rows are the plain 64
+// values of a k-step (128 bytes) with their eight 16-byte chunks permuted by the row number (chunk c of row i at place
+// c ^ (i & 7)): an instruction's 64 lanes fill 8 whole rows, each lane fetching the chunk that belongs at its place, and
+// the B-fragment reads (16 rows, one chunk each) spread over all banks.  Loads return in order, and a step's slice
+// requests are issued ahead of its weight requests, so "all but the newer steps' loads have returned" (one counter
+// wait before the block barrier) covers the slice.
+// Measured at 4B shapes (us per launch incl. the finishing launch, slices through registers / straight to LDS): 128 rows:
+// gate/up 42.5 / 40.7, down 26.7 / 26.0, QKV 23.9 / 23.6, O 20.4 / 19.8; 64 rows: gate/up 30.2 / 31.3, down 18.5 / 18.8,
+// QKV 18.3 / 19.8, O 13.4 / 14.0 - so only the 128-row kernels take the direct path (3 k-steps in flight instead of 2).
+constexpr bool gemm_uses_dma(int cg) { return cg >= 8; }
+constexpr int gemm_pf(int cg) { return cg >= 8 ? 3 : (cg >= 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF); }
+// dynamic LDS of a launch (bytes): the ring of activation slices
+constexpr size_t gemm_dyn_lds(int cg) { return gemm_uses_dma(cg) ? (size_t)(gemm_pf(cg) + 1) * 2 * cg * 16 * 64 * 2 : 0; }
+
 template <int EPI, bool NORM, int CG, bool SPLITK>
 __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(
     // what the prologue needs first, as leading scalars: they arrive in registers with the wave (kernel-argument preload), the
@@ -63,13 +81,20 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(
   constexpr int BM = CG * 16;            // activation rows (MFMA columns) per pass
   // k-steps in flight: 3; 2 with 64 and more rows, where the accumulators leave fewer registers (measured at 4B shapes, 64 rows:
   // gate/up 37.4 against 38.8 us, QKV 19.9 against 21.9)
-  constexpr int PF = CG >= 4 ? (DMTD_GEMM_PF < 2 ? DMTD_GEMM_PF : 2) : DMTD_GEMM_PF;
-  constexpr int LDB = 72;                // LDS row: 64 values + 8 of padding
+  constexpr bool DMA = gemm_uses_dma(CG);
+  constexpr int PF = gemm_pf(CG);
+  constexpr int LDB = 72;                // LDS row (register-staged slices): 64 values + 8 of padding
   constexpr int NT = 64 * GEMM_WAVES;
   constexpr int PIECES = 2 * BM * 8;     // 16-byte pieces of one k-step's activation slice (2 planes)
   constexpr int PPT = PIECES / NT;       // per thread
   static_assert(PIECES % NT == 0, "pieces per thread");
-  __shared__ __attribute__((aligned(16))) bf16_t bs[2][2][BM][LDB];    // [buffer][plane][row][k]
+  constexpr int NBUF = PF + 1;           // DMA: slices in the ring
+  constexpr int SLICE = 2 * BM * 64;     // DMA: bf16 elements of a slice (both planes, rows of 64)
+  constexpr int LPS = PPT + 4;           // loads a thread issues per k-step (slice pieces, then 2 tiles x 2 halves of weights)
+  static_assert(!DMA || (PF - 1) * LPS <= 63, "the counter wait has 6 bits");
+  __shared__ __attribute__((aligned(16))) bf16_t bs[2][2][DMA ? 1 : BM][LDB];    // [buffer][plane][row][k] (register-staged slices)
+  extern __shared__ float4 gemm_dyn_smem[];
+  bf16_t* ring = (bf16_t*)gemm_dyn_smem;                                         // DMA: [NBUF][plane][row][64], chunks permuted
   __shared__ float rs_s[BM];
   __shared__ unsigned long long key_s[BM];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -101,16 +126,34 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(
   int bdst[PPT];
 #pragma unroll
   for (int i = 0; i < PPT; ++i) {
-    const int q = tid + i * NT, plane = q / (BM * 8), row = (q >> 3) % BM, c8 = q & 7;
-    bsrc[i] = (plane ? xb_lo_ : xb_) + (size_t)min(row, M - 1) * ldxb_ + c8 * 8;
-    bdst[i] = (plane * BM + row) * LDB + c8 * 8;
+    if (DMA) {
+      // instruction J = w * PPT + i of a slice fills the 8 rows 8 J .. 8 J + 7 of the plane-major row space; this lane lands at
+      // (row 8 J + lane / 8, place lane % 8) and therefore fetches chunk place ^ (row & 7) of that row
+      const int J = w * PPT + i, plane = J / (BM / 8), row = (J % (BM / 8)) * 8 + (lane >> 3), c8 = (lane & 7) ^ (lane >> 3);
+      bsrc[i] = (plane ? xb_lo_ : xb_) + (size_t)min(row, M - 1) * ldxb_ + c8 * 8;
+      bdst[i] = J * 512;                   // the instruction's LDS base inside a slice (elements): wave-uniform
+    } else {
+      const int q = tid + i * NT, plane = q / (BM * 8), row = (q >> 3) % BM, c8 = q & 7;
+      bsrc[i] = (plane ? xb_lo_ : xb_) + (size_t)min(row, M - 1) * ldxb_ + c8 * 8;
+      bdst[i] = (plane * BM + row) * LDB + c8 * 8;
+    }
   }
 
   u32x4 A[PF][2][2];     // [slot][tile][half of the k-step]
-  u32x4 Bq[PF][PPT];
+  u32x4 Bq[DMA ? 1 : PF][PPT];
+  int buf_issue = 0;     // DMA: ring slice the next issue fills (advances with every issue)
   auto issue_always = [&](int s, int slot) {      // slot is a compile-time constant at every call
+    if constexpr (DMA) {
+      bf16_t* dst = ring + buf_issue * SLICE;
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) Bq[slot][i] = *(const u32x4*)(bsrc[i] + (size_t)s * 64);
+      for (int i = 0; i < PPT; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(bsrc[i] + (size_t)s * 64),
+                                         (__attribute__((address_space(3))) void*)(dst + bdst[i]), 16, 0, 0);
+      buf_issue = buf_issue + 1 == NBUF ? 0 : buf_issue + 1;
+    } else {
+#pragma unroll
+      for (int i = 0; i < PPT; ++i) Bq[slot][i] = *(const u32x4*)(bsrc[i] + (size_t)s * 64);
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       A[slot][j][0] = __builtin_nontemporal_load((const u32x4*)(abase[j] + (size_t)s * 1024));
@@ -150,19 +193,36 @@ __global__ void __launch_bounds__(64 * gemm_waves(CG, EPI)) gemm_mfma_kernel(
 #pragma unroll
     for (int g = 0; g < CG; ++g) acc[j][g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  int buf_use = 0;       // DMA: ring slice of the step at hand
+  // DMA: this lane's two chunks of a B fragment row (k halves 0 and 1), permuted as the slices are stored
+  const int rd0 = r * 64 + ((kg ^ (r & 7)) << 3), rd1 = r * 64 + (((4 + kg) ^ (r & 7)) << 3);
   auto step = [&](int s, int slot, auto mode_c) {
     constexpr int MODE = decltype(mode_c)::value;
-    bf16_t* buf = &bs[s & 1][0][0][0];
+    bf16_t* buf;
+    if constexpr (DMA) {
+      buf = ring + buf_use * SLICE;
+      buf_use = buf_use + 1 == NBUF ? 0 : buf_use + 1;
+      // this step's slice pieces (requested ahead of its weights, PF steps ago) have landed once all loads but those of
+      // the PF - 1 newer steps have returned; with nothing newer on its way for certain (the tail), all loads
+      // the barrier is the bare instruction: the block-wide fence of __syncthreads would wait for every load in flight, the
+      // newer steps' included (the slice requests count as writes to LDS)
+      constexpr int VM = MODE == 1 ? (PF - 1) * LPS : 0;
+      __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (7 << 4));       // vmcnt(VM) lgkmcnt(0), expcnt untouched
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");      // no LDS read of the slice moves above the barrier
+    } else {
+      buf = &bs[s & 1][0][0][0];
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) *(u32x4*)(buf + bdst[i]) = Bq[slot][i];
-    __syncthreads();
+      for (int i = 0; i < PPT; ++i) *(u32x4*)(buf + bdst[i]) = Bq[slot][i];
+      __syncthreads();
+    }
 #pragma unroll
     for (int g = 0; g < CG; ++g) {
 #pragma unroll
       for (int plane = 1; plane >= 0; --plane) {
-        const bf16_t* row = buf + (plane * BM + g * 16 + r) * LDB + kg * 8;
+        const bf16_t* row = DMA ? buf + (plane * BM + g * 16) * 64 + rd0 : buf + (plane * BM + g * 16 + r) * LDB + kg * 8;
         const bf16x8_t b0 = __builtin_bit_cast(bf16x8_t, *(const u32x4*)row);
-        const bf16x8_t b1 = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(row + 32));
+        const bf16x8_t b1 = __builtin_bit_cast(bf16x8_t, *(const u32x4*)(DMA ? row - rd0 + rd1 : row + 32));
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           acc[j][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[slot][j][0]), b0, acc[j][g], 0, 0, 0);
