@@ -222,7 +222,7 @@ def test_masked_forward_equals_c3_cycle_decoding(model_4b):
     for pos in range(P, n):
         eng.decode_cycle(wl.tau, wl.n_late, max_new=1, forced=toks[:, pos:pos + 1])
         worst = max(worst, norm_err(eng.logits()[0], one["logits"][0, pos].astype(np.float64)))
-    # the two paths carry different row counts through the projections (16-position chunks vs 1 or 3 rows), so
+    # the two paths carry different row counts through the projections (128-position passes vs 1 or 3 rows), so
     # they differ by the bf16 storage noise of the caches, well inside the tolerance against the oracle
     assert worst < 0.5 * TOL_BF16, worst
     print(f"C3 one-shot masked forward vs cycle decoding: worst {worst:.2e}")

@@ -32,8 +32,10 @@ CASES = {
     "bf16_eq3_tau3": (di.ModelShape(4, 256, 8, 2, 128, 512, 1000, dtype="bf16"), 2, 70, 3, 0, 2, None),
     "bf16_infer_hd64": (di.ModelShape(3, 128, 4, 2, 64, 256, 515, dtype="bf16"), 1, 45, 2, 0, 1, 30),
     "bf16_exdy_e1d2": (di.ModelShape(6, 256, 8, 2, 128, 512, 1000, dtype="bf16"), 1, 40, 3, 1, 2, 20),
-    # 5 sequences x 16 positions = 80 rows per chunk: two passes of the tiled projection kernel, ragged vocabulary
+    # 5 sequences x 25 positions = 125 rows per pass (one 128-row pass of the tiled projection kernel), ragged vocabulary
     "bf16_batch5_two_passes": (di.ModelShape(2, 128, 4, 2, 64, 256, 203, dtype="bf16"), 5, 35, 4, 0, 1, None),
+    # 9 sequences x 16 positions = 144 rows per pass: two weight passes of the tiled kernel (128 + 16 rows)
+    "bf16_batch9_two_weight_passes": (di.ModelShape(2, 128, 4, 2, 64, 256, 203, dtype="bf16"), 9, 35, 4, 0, 1, None),
 }
 
 
