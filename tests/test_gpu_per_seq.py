@@ -161,3 +161,47 @@ def test_per_sequence_cycles_at_the_4b_shape():
         o.prefill(prompts[b])
     worst, checked = run_calls(eng, orcs, toks, [([3, 2], 5), ([3, 2], 4)], n_late, TOL_BF16)
     print(f"per-sequence cycles at the 4B shape: worst {worst:.2e}, tokens checked {checked}")
+
+
+@pytest.mark.parametrize("name", ["fp32", "bf16"])
+def test_prompts_of_different_lengths_with_cycle_lengths_per_sequence(name):
+    """dmtd_prefill_ragged followed by dmtd_decode_per_seq: every sequence has its own positions AND its own cycle
+    boundaries; each against a standalone oracle run with its own prompt and cycle lengths, caches included."""
+    sh = (di.ModelShape(4, 64, 4, 2, 64, 96, 61, dtype="fp32") if name == "fp32"
+          else di.ModelShape(4, 256, 8, 2, 128, 512, 1000, dtype="bf16"))
+    lengths = [9, 20, 33, 17] if name == "fp32" else [300, 270, 41, 150]
+    taus = [3, 2, 4, 1]
+    B, P, n_late, steps = len(lengths), max(lengths), 2, 13
+    tol = TOL_F32 if sh.dtype == "fp32" else TOL_BF16
+    blob = di.make_weight_blob(sh, seed=17, std=0.05 if sh.dtype == "fp32" else 0.03, gain_sigma=0.2)
+    full = di.make_prompts(sh.vocab, B, P + steps + 4, seed=8)
+    padded = np.full((B, P), sh.vocab - 1, np.int32)
+    for b, n in enumerate(lengths):
+        padded[b, :n] = full[b, :n]
+    eng = pkg.Engine(engine_config(sh, P + steps + 8, B), blob)
+    ocfg = oracle_config(sh)
+    w = O.unpack_weights(blob, ocfg)
+    orcs = [O.DmtdOracle(ocfg, w, P + steps + 8) for _ in range(B)]
+    eng.prefill(padded, lengths=lengths)
+    for b, o in enumerate(orcs):
+        o.prefill(full[b, :lengths[b]])
+    worst, checked, done = 0.0, 0, 0
+    for n in (4, 1, 8):
+        f = np.stack([full[b, lengths[b] + done:lengths[b] + done + n] for b in range(B)])
+        out = eng.decode_per_seq(taus, n_late, n, forced=f)
+        z = eng.logits()
+        for b, o in enumerate(orcs):
+            refs = oracle_steps(o, taus[b], n_late, f[b].tolist())
+            for i, ref in enumerate(refs):
+                if top2_margin(ref.astype(np.float64)) > MARGIN:
+                    assert int(out[b, i]) == int(np.argmax(ref)), (b, i)
+                    checked += 1
+            worst = max(worst, norm_err(z[b], refs[-1].astype(np.float64)))
+            s = eng.seq_state(b)
+            shift = P - lengths[b]                          # the engine counts in the longest sequence's coordinates
+            assert (eng.state()["n_tok"] - shift, s["n_front"] - shift, s["phase"]) == (o.n_tok, o.n_front, o.phase), b
+        done += n
+    assert worst < tol, worst
+    assert checked > 0
+    compare_caches(eng, orcs, sh, n_late, 1e-5 if sh.dtype == "fp32" else 2e-2)
+    print(f"ragged prompts + per-sequence cycles {name}: worst {worst:.2e}, tokens checked {checked}")
