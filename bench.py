@@ -167,6 +167,10 @@ def main():
     for kind, r in (("gateup", rows), ("gateup", rows_late), ("down", rows), ("down", rows_late), ("qkv", rows), ("qkv", rows_late),
                     ("oproj", rows), ("oproj", rows_late), ("lmhead", B), ("attn", 1), ("attn", r_seq)):
         per[f"{kind}_m{r}"] = eng.time_kernel(kind, r, reps)
+    # what a launch that only reads the same weight bytes takes (no activations, no arithmetic, no output)
+    read_only = {}
+    if sh.elem_bytes == 2:
+        read_only = {k: eng.time_kernel("read_" + k, 1, reps) for k in ("gateup", "down", "qkv", "oproj")}
     # the same kernel times summed over one cycle's launches (full step: front layers with the refill rows, late layers
     # and LM head with one row per sequence; tau-1 late-only steps), to set beside ms_per_step
     layer_full = sum(per[f"{k}_m{rows}"] for k in ("qkv", "oproj", "gateup", "down")) + per[f"attn_m{r_seq}"]
@@ -183,6 +187,9 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "bytes_per_launch": gu_bytes, "avg_launch_us": round(per[f"gateup_m{rows}"], 2),
                 "other_kernels_us": {k: round(v, 2) for k, v in per.items()}}
+    if read_only:
+        roofline["read_only_kernel_us"] = {k: round(v, 2) for k, v in read_only.items()}
+        roofline["frac_of_read_only_kernel"] = round(read_only["gateup"] / per[f"gateup_m{rows}"], 4)
     if rows > 16:
         # batched steps run on the matrix cores in earnest: flops of the same launch (two bf16 activation planes, so
         # 2 x 2 x rows x N x K multiply-adds) against the dense bf16 peak; the launch stays bound by the weight stream

@@ -228,6 +228,13 @@ int dmtd_read_kv(dmtd_ctx* ctx, int32_t layer, int32_t b, int32_t n_pos, float* 
 #define DMTD_K_DOWN    3   /* down projection + residual */
 #define DMTD_K_LMHEAD  4   /* final RMSNorm + LM head (Eq. 5) + argmax partials */
 #define DMTD_K_ATTN    5   /* split-K GQA decode attention over the current context */
+/* Kinds that only read: one launch per layer of a kernel that streams exactly the weight bytes of that projection
+ * (as stored) and does nothing else; `rows` is ignored (pass 1).  bf16 models only (DMTD_EINVAL otherwise).  What a
+ * plain read of the same bytes costs on the chip, to set beside the kernel that does the work. */
+#define DMTD_K_READ_QKV    6
+#define DMTD_K_READ_OPROJ  7
+#define DMTD_K_READ_GATEUP 8
+#define DMTD_K_READ_DOWN   9
 int dmtd_time_kernel(dmtd_ctx* ctx, int32_t kind, int32_t rows, int32_t reps, float* avg_us);
 
 /* ExDy variant (Sec. 2.1, the paragraph before Eq. 5; layer allocations of Sec. 3.3): the in-cycle tokens

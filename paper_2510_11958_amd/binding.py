@@ -294,7 +294,8 @@ class Engine:
         self._check(self.lib.dmtd_read_kv(self._h, layer, b, n_pos, out.ctypes.data_as(C.POINTER(C.c_float)), out.size))
         return out
 
-    KERNEL_KINDS = {"qkv": 0, "oproj": 1, "gateup": 2, "down": 3, "lmhead": 4, "attn": 5}
+    KERNEL_KINDS = {"qkv": 0, "oproj": 1, "gateup": 2, "down": 3, "lmhead": 4, "attn": 5,
+                    "read_qkv": 6, "read_oproj": 7, "read_gateup": 8, "read_down": 9}
 
     def time_kernel(self, kind: str, rows: int = 1, reps: int = 5) -> float:
         """Average duration (microseconds) of one launch of a kernel kind, HIP-event timed on the engine's stream."""

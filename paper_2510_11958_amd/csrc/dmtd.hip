@@ -1124,6 +1124,21 @@ hipError_t time_one(dmtd_ctx* c, int kind, int l, int rows) {
   Rows R = front_rows(c);
   float* qkv = (float*)(c->ws + c->o.qkv);
   const LayerW& w = c->layers[l];
+  if (kind >= DMTD_K_READ_QKV && kind <= DMTD_K_READ_DOWN) {
+    // nothing but a read of the bytes the projection of that kind streams for layer l (the stored weight image)
+    const LayerSw& s = c->sw[l];
+    const bf16_t *p0 = nullptr, *p1 = nullptr;
+    size_t n0 = 0, n1 = 0;                       // 16-byte units
+    switch (kind) {
+      case DMTD_K_READ_QKV:    p0 = s.qkv;  n0 = swizzled_elems(nqkv, d) / 8; break;
+      case DMTD_K_READ_OPROJ:  p0 = s.o;    n0 = swizzled_elems(d, qd) / 8; break;
+      case DMTD_K_READ_GATEUP: p0 = s.gate; n0 = swizzled_elems(ff, d) / 8; p1 = s.up; n1 = n0; break;
+      default:                 p0 = s.down; n0 = swizzled_elems(d, ff) / 8; break;
+    }
+    hipLaunchKernelGGL(read_only_kernel, dim3(2048), dim3(256), 0, c->stream, (const u32x4*)p0, n0, (const u32x4*)(p1 ? p1 : p0), n1,
+                       (u32x4*)qkv);
+    return hipGetLastError();
+  }
   if (kind == DMTD_K_ATTN) {
     // attention for `rows` query rows per sequence ending at the newest cached position
     const int last = c->sched.n_tok - 1;
@@ -1810,9 +1825,10 @@ int dmtd_time_kernel(dmtd_ctx* c, int32_t kind, int32_t rows, int32_t reps, floa
   if (!c) return DMTD_EINVAL;
   // attention: rows per sequence (at most 16); projections: total activation rows (at most max_batch * 16, the row buffers' capacity)
   const int rows_max = kind == DMTD_K_ATTN ? kMaxRows : row_capacity(c->cfg.max_batch);
-  if (!avg_us || kind < 0 || kind > DMTD_K_ATTN || rows < 1 || rows > rows_max || reps < 1) {
+  if (!avg_us || kind < 0 || kind > DMTD_K_READ_DOWN || rows < 1 || rows > rows_max || reps < 1) {
     c->err = "bad argument to dmtd_time_kernel"; return DMTD_EINVAL;
   }
+  if (kind >= DMTD_K_READ_QKV && !c->packed) { c->err = "the read-only kinds need a bf16 model (they read its stored weight image)"; return DMTD_EINVAL; }
   if (c->cfg.dry_run || c->sched.n_tok == 0) { c->err = "dmtd_time_kernel needs a prefilled context"; return DMTD_ESTATE; }
   if (kind == DMTD_K_LMHEAD && rows > c->batch) { c->err = "the LM head carries one row per sequence"; return DMTD_EINVAL; }
   hipEvent_t e0, e1;

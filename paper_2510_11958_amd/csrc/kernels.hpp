@@ -130,6 +130,27 @@ __global__ void emitted_to_rows_kernel(const int* __restrict__ emitted, int* __r
   for (int i = threadIdx.x; i < n_steps * batch; i += blockDim.x) out[(size_t)(i % batch) * out_stride + i / batch] = emitted[i];
 }
 
+// Reads two byte ranges (16-byte units) and does nothing else: what a launch that only streams the same bytes costs
+// on this chip, to set beside the projection kernels.  Grid-stride, four independent 16-byte loads per thread in flight,
+// streaming (non-temporal) loads.  The store never happens for data that is not all one magic pattern; it only keeps the loads alive.
+__global__ void __launch_bounds__(256) read_only_kernel(const u32x4* __restrict__ p0, size_t n0, const u32x4* __restrict__ p1, size_t n1,
+                                                        u32x4* sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int range = 0; range < 2; ++range) {
+    const u32x4* __restrict__ p = range ? p1 : p0;
+    const size_t n = range ? n1 : n0;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+      const u32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + stride);
+      const u32x4 c = __builtin_nontemporal_load(p + i + 2 * stride), d = __builtin_nontemporal_load(p + i + 3 * stride);
+      acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n; i += stride) acc ^= __builtin_nontemporal_load(p + i);
+  }
+  if (acc.x == 0x9e3779b9u && acc.y == 0x7f4a7c15u && acc.z == 0xf39cc060u && acc.w == 0x5cedc834u) sink[0] = acc;
+}
+
 __global__ void zero_u64_kernel(unsigned long long* p, int n) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0ull;
 }
