@@ -136,3 +136,52 @@ def test_a_failed_call_can_be_repeated(entry, monkeypatch):
         for b in range(B):
             assert np.array_equal(bad.read_kv(l, b, nt), good.read_kv(l, b, nt))
     assert bad.trace() == good.trace()
+
+
+@pytest.mark.parametrize("dtype,max_seq_len,P", [("fp32", 45, 7), ("bf16", 531, 490)])
+def test_decoding_into_the_last_cache_slot_and_not_beyond(dtype, max_seq_len, P):
+    """The cache's maximum size: cycles run until the last position of the cache is written (bf16 case: the context
+    crosses a 512-key bucket whose end lies beyond the cache), every call checked against the oracle; one more step is
+    refused with DMTD_ECAPACITY and leaves the state alone; a cycle that does not fit whole is refused, its first step
+    alone is not."""
+    sh = (di.ModelShape(3, 128, 4, 1, 128, 200, 130, dtype="fp32") if dtype == "fp32"
+          else di.ModelShape(3, 256, 4, 2, 64, 512, 700, dtype="bf16"))
+    B, tau, n_late = 2, 3, 1
+    blob = di.make_weight_blob(sh, seed=3)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=5)
+    toks = forced_string(sh.vocab, B, prompts, max_seq_len + 1)
+    p = Pair(sh, blob, max_seq_len, batch=B)
+    p.prefill(prompts)
+    tol = TOL_F32 if dtype == "fp32" else TOL_BF16
+    worst = 0.0
+    while p.eng.state()["n_tok"] < max_seq_len:
+        nt = p.eng.state()["n_tok"]
+        n = min(7, max_seq_len - nt)
+        if max_seq_len - nt == 1:
+            # one slot left: a whole cycle of tau steps does not fit (only when the next step opens a cycle), its first step does
+            if p.eng.state()["phase"] >= tau:
+                with pytest.raises(pkg.DmtdError) as e:
+                    p.eng.decode_cycle(tau, n_late)
+                assert e.value.code == pkg.DMTD_ECAPACITY
+                assert p.eng.state()["n_tok"] == nt
+        f = np.stack([toks[b][nt:nt + n] for b in range(B)])
+        out = p.eng.decode(tau, n_late, n, forced=f)
+        z = p.eng.logits()
+        for b, o in enumerate(p.orcs):
+            done = 0
+            while done < n:
+                done += len(o.decode_cycle(tau, n_late, max_new=n - done, forced=f[b][done:].tolist()))
+            ref = o.last_logits.astype(np.float64)
+            worst = max(worst, norm_err(z[b], ref))
+            if top2_margin(ref) > MARGIN:
+                assert int(out[b, -1]) == int(np.argmax(ref))
+    s = p.eng.state()
+    assert s["n_tok"] == max_seq_len == p.orcs[0].n_tok
+    assert worst < tol, worst
+    p.compare_kv(1e-5 if dtype == "fp32" else 2e-2)
+    for call in (lambda: p.eng.decode(tau, n_late, 1), lambda: p.eng.decode_cycle(tau, n_late, max_new=1)):
+        with pytest.raises(pkg.DmtdError) as e:
+            call()
+        assert e.value.code == pkg.DMTD_ECAPACITY
+        assert p.eng.state() == s
+    print(f"{dtype}: cache of {max_seq_len} positions filled, worst {worst:.2e}")
