@@ -205,3 +205,47 @@ def test_prompts_of_different_lengths_with_cycle_lengths_per_sequence(name):
     assert checked > 0
     compare_caches(eng, orcs, sh, n_late, 1e-5 if sh.dtype == "fp32" else 2e-2)
     print(f"ragged prompts + per-sequence cycles {name}: worst {worst:.2e}, tokens checked {checked}")
+
+
+@pytest.mark.parametrize("use_graphs", [True, False])
+def test_more_step_patterns_than_the_device_table_keeps(use_graphs):
+    """A context keeps a bounded table of step patterns (which sequences open a cycle, with how many rows) on the device;
+    patterns beyond it go through a shared slot, without a graph.  Six sequences whose cycle lengths change from call to
+    call produce more distinct patterns than the table holds (counted here from the oracles' own state); every call must
+    still match the per-sequence oracles, the caches at the end."""
+    sh = di.ModelShape(3, 128, 4, 2, 64, 192, 130, dtype="fp32")
+    B, P, n_late, total = 6, 5, 1, 330
+    blob = di.make_weight_blob(sh, seed=3)
+    prompts = di.make_prompts(sh.vocab, B, P, seed=5)
+    toks = forced_string(sh.vocab, B, prompts, P + total + 2)
+    eng = pkg.Engine(engine_config(sh, P + total + 2, B, use_graphs=use_graphs), blob)
+    ocfg = oracle_config(sh)
+    w = O.unpack_weights(blob, ocfg, np.float64)
+    orcs = [O.DmtdOracle(ocfg, w, P + total + 2, np.float64) for _ in range(B)]
+    eng.prefill(prompts)
+    for b, o in enumerate(orcs):
+        o.prefill(prompts[b])
+    rng = np.random.default_rng(17)
+    patterns = set()
+    worst, checked, done = 0.0, 0, 0
+    while done < total:
+        taus = [int(t) for t in rng.integers(1, 6, size=B)]
+        n = int(min(rng.integers(1, 7), total - done))
+        # the patterns this call's steps will have, from the oracles' state: a sequence opens a cycle when its own is complete
+        sim = [(o.phase, o.n_tok - o.n_front) for o in orcs]
+        for _ in range(n):
+            pat, nxt = [], []
+            for b, (ph, pend) in enumerate(sim):
+                if ph >= taus[b]:
+                    pat.append(pend + 1); nxt.append((1, 0))
+                else:
+                    pat.append(0); nxt.append((ph + 1, pend + 1))
+            if len(set(pat)) > 1:
+                patterns.add(tuple(pat))
+            sim = nxt
+        w_, c_ = run_calls(eng, orcs, toks, [(taus, n)], n_late, TOL_F32)
+        worst, checked, done = max(worst, w_), checked + c_, done + n
+    assert len(patterns) > 64, len(patterns)
+    assert checked > 0
+    compare_caches(eng, orcs, sh, n_late, 1e-5)
+    print(f"{len(patterns)} distinct mixed patterns, graphs={use_graphs}: worst {worst:.2e}, tokens checked {checked}")
